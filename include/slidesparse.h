@@ -1,0 +1,130 @@
+/*
+ * slidesparse.h -- C ABI of the MI355X (gfx950) SlideSparse linear-layer library.
+ *
+ * The library computes the (2N-2):2N structured-sparse linear layer
+ *        Y[M,O] = X[M,K] . W[O,K]^T
+ * using only 2:4-sparse matrix instructions, following the paper's problem statement
+ * (Sec. 3.1, goal equation  w^T x = Phi(w)^T Psi(x)):
+ *   Phi  = Sliding Window Decomposition of the weights   (Sec. 3.2, Alg. 2)  -> slide_decompose
+ *   Psi  = Activation Lifting fused into per-token quantisation (Sec. 3.3, Alg. 1) -> act_lift_quant
+ *   2:4 sparse GEMM over the lifted width K' = K*2(N-1)/N (Sec. 4.3)        -> slide_sparse_gemm
+ *   dense GEMM at the original K, the baseline of every speed-up (Sec. 5.1)  -> dense_gemm
+ *
+ * Symbols: M tokens, K input features, O output features, N pattern parameter of
+ * the (2N-2):2N pattern (N = 2 is native 2:4), K' the lifted width.
+ *
+ * Conventions for every call
+ *   - every data pointer is a DEVICE pointer owned by the caller; the library never
+ *     allocates, frees or keeps a pointer after the call returns;
+ *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default
+ *     stream) and the call returns without synchronising;
+ *   - arguments are validated on the host before anything is enqueued; a bad argument
+ *     returns an error code and enqueues nothing; there are no exceptions or aborts;
+ *   - outputs are overwritten completely; inputs are read-only and must not alias
+ *     outputs;
+ *   - all matrices are row-major and dense unless a leading dimension is given.
+ */
+#ifndef SLIDESPARSE_H
+#define SLIDESPARSE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    SS_OK = 0,
+    SS_ERR_NULL = 1,           /* a required pointer is NULL                                  */
+    SS_ERR_BAD_PATTERN_N = 2,  /* N outside 2..8                                              */
+    SS_ERR_SHAPE = 3,          /* a size is non-positive or violates a divisibility rule      */
+    SS_ERR_DTYPE = 4,          /* unknown or unsupported dtype for this call                  */
+    SS_ERR_WORKSPACE = 5,      /* reserved                                                    */
+    SS_ERR_HIP = 6             /* the HIP runtime reported an error at launch                 */
+} ss_status;
+
+/* operand storage type of the GEMM inputs */
+typedef enum {
+    SS_I8 = 0,        /* int8, symmetric, Qmax = 127, int32 accumulation                      */
+    SS_FP8_E4M3 = 1,  /* OCP e4m3fn byte, Qmax = 448, fp32 accumulation                       */
+    SS_BF16 = 2       /* bfloat16, unscaled, fp32 accumulation                                */
+} ss_dtype;
+
+/* storage type of the un-quantised activations / weights handed to the quantisers */
+typedef enum { SS_IN_F32 = 0, SS_IN_BF16 = 1 } ss_act_dtype;
+
+/* K' = K * 2(N-1)/N, the lifted width (Sec. 3.4, expansion factor gamma = 2 - 2/N).
+ * Returns -1 if N is outside 2..8 or K is not a positive multiple of 2N. */
+int64_t slide_lifted_k(int64_t K, int N);
+
+/* Byte sizes of the two buffers slide_decompose writes for an [O,K] weight matrix.
+ * The packed layout is opaque (ordered for the sparse matrix instruction's operand and
+ * index registers); rows are padded to a multiple of 128.  vals_bytes is about
+ * (N-1)/N and meta_bytes (N-1)/(4N) (8-bit) of the dense weight bytes. */
+ss_status slide_packed_sizes(int64_t O, int64_t K, int N, ss_dtype dtype,
+                             size_t* vals_bytes, size_t* meta_bytes);
+
+/* Offline weight preparation (Sec. 4.1 "prune", App. E magnitude pruning; per-output-
+ * channel symmetric quantisation as in Alg. 1 pass 1): for every row o of W[O,K] keep the
+ * 2N-2 largest-|w| entries of each aligned run of 2N (ties keep the lower index), then
+ * s_w[o] = max|w|/Qmax and Wq = clamp(rne(w * (Qmax/max|w|))) (BF16: rne to bf16, s_w
+ * untouched and may be NULL).  W is fp32 or bf16 (in_dtype).  An all-zero row gets
+ * s_w = 1. */
+ss_status slide_prune_quant(const void* W, ss_act_dtype in_dtype, int64_t O, int64_t K, int N,
+                            ss_dtype dtype, void* Wq, float* s_w, void* stream);
+
+/* Sliding Window Decomposition + 2:4 compression (Sec. 3.2, Alg. 2; Sec. 4.3).
+ * Wq[O,K] holds quantised weights obeying the (2N-2):2N pattern (at most 2N-2 non-zeros
+ * per aligned run of 2N along K; +-0 count as zero for fp8/bf16).  Each 2N block is
+ * rewritten as N-1 stride-2 windows of 4 by the greedy residual allocation (window order
+ * g, l ascending; inside a window the first <=2 unused non-zeros in ascending position),
+ * every window is stored as 2 values + two 2-bit positions, and the result is laid out
+ * for slide_sparse_gemm.  Requires K % 2N == 0 and K' % 128 == 0 (SS_ERR_SHAPE otherwise).
+ * violations (nullable, device int32, must be zeroed by the caller): incremented once
+ * per 2N block that holds more than 2N-2 non-zeros; output is unspecified for such blocks. */
+ss_status slide_decompose(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype,
+                          void* w_vals, void* w_meta, int32_t* violations, void* stream);
+
+/* Same decomposition in a plain, documented form for inspection and parity tests:
+ * vals[O, K'/2] (dtype) and idx[O, K'/4] bytes, one per window = i0 | i1 << 2 with
+ * i0 < i1 the positions (0..3) of the two stored values; a window with fewer than two
+ * non-zeros stores value 0 at the lowest positions not holding a non-zero. */
+ss_status slide_decompose_canonical(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype,
+                                    void* vals, uint8_t* idx, int32_t* violations, void* stream);
+
+/* Fused quantisation + slide (Alg. 1).  X[M,K] with row stride ldx (elements), fp32 or
+ * bf16.  Per token i: a = max_k |x|, s_x[i] = a/Qmax, r = Qmax/a (fp32), and for every
+ * output window j = g(N-1)+l the four elements at b = 2N g + 2l are quantised as
+ * clamp(rne(x*r), +-Qmax) and stored at X_lifted[i, 4j .. 4j+3].  out = SS_BF16: no
+ * scaling, elements are rounded (rne) to bf16 and s_x may be NULL.  N = 2 is plain
+ * per-token quantisation (K' = K).  An all-zero token gets s_x = 1 and zeros.
+ * X_lifted is [M, K'] dense.  Requires K % 2N == 0. */
+ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_t K, int64_t ldx,
+                         int N, ss_dtype out, void* X_lifted, float* s_x, void* stream);
+
+/* 2:4 sparse GEMM over the lifted width (Sec. 4.3) with the scale epilogue:
+ *   Y[m,o] = bf16( (fp32(acc[m,o]) * s_x[m]) * s_w[o] ),  acc = sum over K' of X' . W'
+ * (SS_BF16: Y = bf16(acc), s_x and s_w ignored and may be NULL).  X_lifted[M,K_lifted]
+ * dense row-major from act_lift_quant; w_vals/w_meta from slide_decompose for the same
+ * O and K_lifted.  Y is bf16 [M,O] with row stride ldy (elements, >= O).
+ * Requires K_lifted % 128 == 0. */
+ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, const void* w_vals,
+                            const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                            int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy, void* stream);
+
+/* Dense baseline at the original K with the same epilogue: Xq[M,K], Wq[O,K] row-major.
+ * Requires K % 128 == 0. */
+ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq, const float* s_w,
+                     int64_t M, int64_t O, int64_t K, ss_dtype dtype, void* Y, int64_t ldy,
+                     void* stream);
+
+const char* ss_status_string(ss_status s);
+
+/* Library / packed-format version (bumped whenever the opaque layout changes). */
+int slide_format_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SLIDESPARSE_H */

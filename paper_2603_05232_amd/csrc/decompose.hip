@@ -1,0 +1,166 @@
+// slide_decompose: Sliding Window Decomposition (Alg. 2, greedy residual allocation) fused
+// with 2:4 compression, written output-oriented: one thread produces one lane's worth of
+// sparse-operand registers (16 stored values + one index word), so every store is coalesced.
+// A thread re-runs the greedy over the few earlier windows of the same 2N block to recover
+// the carry; the block is at most 16 elements, so this costs a handful of integer ops.
+#include "ss_common.h"
+#include "packed_layout.h"
+
+namespace ss {
+
+template <int ES> struct Elem;
+template <> struct Elem<1> { typedef uint8_t T; __device__ static bool nz(T v, bool fp) { return fp ? (v & 0x7F) != 0 : v != 0; } };
+template <> struct Elem<2> { typedef uint16_t T; __device__ static bool nz(T v, bool) { return (v & 0x7FFF) != 0; } };
+
+// One window of the decomposition: values and positions (i0 < i1) of window l of block g of a
+// row, plus the block's non-zero count.  `row` points at the row's first element.
+template <int ES>
+__device__ inline void slide_window(const typename Elem<ES>::T* row, int N, int g, int l, bool fp,
+                                    typename Elem<ES>::T& v0, typename Elem<ES>::T& v1, uint32_t& i0, uint32_t& i1, int& nnz)
+{
+    typedef typename Elem<ES>::T T;
+    const T* blk = row + (int64_t)g * 2 * N;
+    uint32_t nzmask = 0;
+    for (int p = 0; p < 2 * l + 4; ++p) nzmask |= (uint32_t)Elem<ES>::nz(blk[p], fp) << p;
+    uint32_t used = 0, taken = 0;
+    for (int w = 0; w <= l; ++w) {                       // greedy, windows in ascending order
+        int cnt = 0;
+        taken = 0;
+        for (int d = 0; d < 4; ++d) {
+            const int p = 2 * w + d;
+            if (((nzmask >> p) & 1u) && !((used >> p) & 1u) && cnt < 2) { used |= 1u << p; taken |= 1u << d; ++cnt; }
+        }
+    }
+    if (l == 0) {                                        // pattern check, once per block
+        uint32_t all = nzmask;
+        for (int p = 4; p < 2 * N; ++p) all |= (uint32_t)Elem<ES>::nz(blk[p], fp) << p;
+        nnz = __popc(all);
+    } else nnz = 0;
+    // pad to two positions with the lowest offsets that hold no stored non-zero
+    uint32_t chosen = taken;
+    for (int d = 0; d < 4 && __popc(chosen) < 2; ++d) chosen |= 1u << d;
+    i0 = __ffs(chosen) - 1;
+    i1 = 31 - __clz(chosen);
+    v0 = ((taken >> i0) & 1u) ? blk[2 * l + i0] : (T)0;
+    v1 = ((taken >> i1) & 1u) ? blk[2 * l + i1] : (T)0;
+}
+
+// canonical form: one thread per (row, window)
+template <int ES>
+__global__ __launch_bounds__(256) void k_decompose_canonical(const typename Elem<ES>::T* __restrict__ Wq, int64_t O, int K, int N, bool fp,
+                                                              typename Elem<ES>::T* __restrict__ vals, uint8_t* __restrict__ idx,
+                                                              int32_t* __restrict__ violations)
+{
+    const int nwin = (K / (2 * N)) * (N - 1);
+    const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (id >= O * nwin) return;
+    const int64_t o = id / nwin;
+    const int j = (int)(id - o * nwin);
+    const int g = j / (N - 1), l = j - g * (N - 1);
+    typename Elem<ES>::T v0, v1; uint32_t i0, i1; int nnz;
+    slide_window<ES>(Wq + o * (int64_t)K, N, g, l, fp, v0, v1, i0, i1, nnz);
+    vals[o * (int64_t)nwin * 2 + 2 * j] = v0;
+    vals[o * (int64_t)nwin * 2 + 2 * j + 1] = v1;
+    idx[o * (int64_t)nwin + j] = (uint8_t)(i0 | (i1 << 2));
+    if (violations && nnz > 2 * N - 2) atomicAdd(violations, 1);
+}
+
+// packed form for 8-bit operands: one thread per (panel, 64-column step, fragment, lane)
+__global__ __launch_bounds__(256) void k_decompose_packed8(const uint8_t* __restrict__ Wq, int64_t O, int K, int N, bool fp,
+                                                            uint4* __restrict__ vals, uint32_t* __restrict__ meta, int64_t nslots,
+                                                            int nsteps, int32_t* __restrict__ violations)
+{
+    const int64_t slot = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (slot >= nslots) return;
+    const int lane = (int)(slot & 63);
+    const int f = (int)((slot >> 6) & 3);
+    const int64_t ps = slot >> 8;
+    const int64_t panel = ps / nsteps;
+    const int step = (int)(ps - panel * nsteps);
+    const int64_t o = panel * PANEL + panel_row(f, lane & 31);
+    const int qa = lane >> 5;
+    uint32_t v[4] = {0, 0, 0, 0};
+    uint32_t m = 0x44444444u;                            // positions (0, 1) everywhere: an all-zero fragment
+    if (o < O) {
+        m = 0;
+        int bad = 0;
+#pragma unroll
+        for (int w = 0; w < 8; ++w) {
+            const int j = step * (FRAG_K8 / 4) + step_window(qa, w);
+            const int g = j / (N - 1), l = j - g * (N - 1);
+            uint8_t v0, v1; uint32_t i0, i1; int nnz;
+            slide_window<1>(Wq + o * (int64_t)K, N, g, l, fp, v0, v1, i0, i1, nnz);
+            v[w >> 1] |= ((uint32_t)v0 | ((uint32_t)v1 << 8)) << (16 * (w & 1));
+            m |= (i0 | (i1 << 2)) << (4 * w);
+            bad += nnz > 2 * N - 2;
+        }
+        if (violations && bad) atomicAdd(violations, bad);
+    }
+    vals[slot] = make_uint4(v[0], v[1], v[2], v[3]);
+    meta[slot] = m;
+}
+
+}  // namespace ss
+
+using namespace ss;
+
+static ss_status check_decompose(int64_t O, int64_t K, int N, ss_dtype dtype)
+{
+    if (!valid_N(N)) return SS_ERR_BAD_PATTERN_N;
+    if (dtype != SS_I8 && dtype != SS_FP8_E4M3 && dtype != SS_BF16) return SS_ERR_DTYPE;
+    if (O < 0 || K <= 0 || K % (2 * N) != 0 || K > (1 << 24) || O > (1 << 24)) return SS_ERR_SHAPE;
+    return SS_OK;
+}
+
+extern "C" ss_status slide_packed_sizes(int64_t O, int64_t K, int N, ss_dtype dtype, size_t* vals_bytes, size_t* meta_bytes)
+{
+    ss_status st = check_decompose(O, K, N, dtype);
+    if (st != SS_OK) return st;
+    if (!vals_bytes || !meta_bytes) return SS_ERR_NULL;
+    const int64_t Kp = lifted_k(K, N);
+    if (Kp % KSTEP != 0) return SS_ERR_SHAPE;
+    if (dtype == SS_BF16) return SS_ERR_DTYPE;          // bf16 packing not built yet
+    const int64_t Opad = (O + PANEL - 1) / PANEL * PANEL;
+    *vals_bytes = (size_t)(Opad * (Kp / 2));
+    *meta_bytes = (size_t)(Opad * (Kp / 8));
+    return SS_OK;
+}
+
+extern "C" ss_status slide_decompose(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype, void* w_vals, void* w_meta,
+                                     int32_t* violations, void* stream)
+{
+    ss_status st = check_decompose(O, K, N, dtype);
+    if (st != SS_OK) return st;
+    const int64_t Kp = lifted_k(K, N);
+    if (Kp % KSTEP != 0) return SS_ERR_SHAPE;
+    if (dtype == SS_BF16) return SS_ERR_DTYPE;
+    if (O == 0) return SS_OK;
+    if (!Wq || !w_vals || !w_meta) return SS_ERR_NULL;
+    const int64_t npanels = (O + PANEL - 1) / PANEL;
+    const int nsteps = (int)(Kp / FRAG_K8);
+    const int64_t nslots = npanels * nsteps * FRAGS_PER_PANEL * 64;
+    hipLaunchKernelGGL(k_decompose_packed8, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const uint8_t*>(Wq), O, (int)K, N, dtype == SS_FP8_E4M3, static_cast<uint4*>(w_vals),
+                       static_cast<uint32_t*>(w_meta), nslots, nsteps, violations);
+    return launch_status();
+}
+
+extern "C" ss_status slide_decompose_canonical(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype, void* vals, uint8_t* idx,
+                                               int32_t* violations, void* stream)
+{
+    ss_status st = check_decompose(O, K, N, dtype);
+    if (st != SS_OK) return st;
+    if (O == 0) return SS_OK;
+    if (!Wq || !vals || !idx) return SS_ERR_NULL;
+    const int64_t nwin = (K / (2 * N)) * (N - 1);
+    const int64_t total = O * nwin;
+    dim3 grid((unsigned)((total + 255) / 256)), block(256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == SS_BF16)
+        hipLaunchKernelGGL(k_decompose_canonical<2>, grid, block, 0, s, static_cast<const uint16_t*>(Wq), O, (int)K, N, true,
+                           static_cast<uint16_t*>(vals), idx, violations);
+    else
+        hipLaunchKernelGGL(k_decompose_canonical<1>, grid, block, 0, s, static_cast<const uint8_t*>(Wq), O, (int)K, N,
+                           dtype == SS_FP8_E4M3, static_cast<uint8_t*>(vals), idx, violations);
+    return launch_status();
+}

@@ -1,0 +1,309 @@
+// act_lift_quant: fused per-token quantisation + activation lifting (Alg. 1), and
+// slide_prune_quant: offline (2N-2):2N magnitude pruning + per-channel quantisation.
+//
+// Both kernels stream a row through one workgroup: the row is read from HBM once, kept in
+// registers while the wavefronts reduce the absmax, quantised element-wise into LDS, and the
+// lifted windows are then gathered from LDS so that every source element is quantised once
+// and every output store is a coalesced 16-byte vector.  HBM traffic per token is therefore
+// the algorithmic minimum: K input elements in, K' output elements + one scale out.
+#include "ss_common.h"
+
+namespace ss {
+
+constexpr int LQ_THREADS = 256;
+
+template <typename T> struct InVec;
+template <> struct InVec<float> {
+    static constexpr int N = 4; typedef float4 V;
+    __device__ static void unpack(const V& v, float* f) { f[0] = v.x; f[1] = v.y; f[2] = v.z; f[3] = v.w; }
+};
+template <> struct InVec<uint16_t> {          // bf16 bits
+    static constexpr int N = 8; typedef uint4 V;
+    __device__ static void unpack(const V& v, float* f)
+    {
+        const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+        for (int i = 0; i < 4; ++i) { f[2 * i] = __uint_as_float(w[i] << 16); f[2 * i + 1] = __uint_as_float(w[i] & 0xFFFF0000u); }
+    }
+};
+__device__ inline float load_scalar(const float* p) { return *p; }
+__device__ inline float load_scalar(const uint16_t* p) { return bf16_bits_to_f32(*p); }
+
+__device__ inline float block_absmax(float v, float* red)
+{
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) red[wave] = v;
+    __syncthreads();
+    float m = red[0];
+#pragma unroll
+    for (int w = 1; w < LQ_THREADS / 64; ++w) m = fmaxf(m, red[w]);
+    return m;
+}
+
+// quantise one element: OUT 0 = int8, 1 = fp8 e4m3, 2 = bf16 (no scale)
+template <int OUT> __device__ inline uint32_t quant1(float x, float r)
+{
+    if constexpr (OUT == 0) {
+        float q = rintf(x * r);
+        q = fminf(fmaxf(q, -127.0f), 127.0f);
+        return (uint32_t)(int)q & 0xFFu;
+    } else if constexpr (OUT == 1) {
+        float q = x * r;
+        q = fminf(fmaxf(q, -448.0f), 448.0f);
+        return f32_to_e4m3(q);
+    } else {
+        return f32_to_bf16_bits(x);
+    }
+}
+
+// MAXV > 0: vector loads, row kept in registers (needs K <= MAXV * LQ_THREADS * VecN, 16-byte
+// aligned rows).  MAXV == 0: scalar loads, second pass re-reads the row.
+template <typename TIN, int OUT, int MAXV>
+__global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __restrict__ X, int64_t ldx, int K, int N,
+                                                                uint8_t* __restrict__ XL, float* __restrict__ s_x, int Kp)
+{
+    constexpr int ES = OUT == 2 ? 2 : 1;                 // output element bytes
+    extern __shared__ uint32_t lds[];                     // K * ES bytes of quantised row + 8 bytes of slack (read, never used)
+    __shared__ float red[LQ_THREADS / 64];
+    const int64_t m = blockIdx.x;
+    const TIN* x = X + m * ldx;
+    const int t = threadIdx.x;
+    typedef InVec<TIN> IV;
+    typename IV::V v[MAXV > 0 ? MAXV : 1];
+    const int nvec = K / IV::N;
+
+    // ---- pass 1: absmax (Alg. 1, dynamic quantisation scale)
+    float amax = 0.0f;
+    if constexpr (MAXV > 0) {
+        const typename IV::V* xv = reinterpret_cast<const typename IV::V*>(x);
+#pragma unroll
+        for (int i = 0; i < MAXV; ++i) {
+            const int idx = t + i * LQ_THREADS;
+            if (idx < nvec) {
+                v[i] = xv[idx];
+                if constexpr (OUT != 2) {
+                    float f[IV::N]; IV::unpack(v[i], f);
+#pragma unroll
+                    for (int e = 0; e < IV::N; ++e) amax = fmaxf(amax, fabsf(f[e]));
+                }
+            }
+        }
+    } else if constexpr (OUT != 2) {
+        for (int k = t; k < K; k += LQ_THREADS) amax = fmaxf(amax, fabsf(load_scalar(x + k)));
+    }
+    float r = 0.0f;
+    if constexpr (OUT != 2) {
+        amax = block_absmax(amax, red);
+        constexpr float QMAX = OUT == 0 ? 127.0f : 448.0f;
+        float s = 1.0f;
+        if (amax > 0.0f) { r = QMAX / amax; s = amax / QMAX; }
+        if (t == 0) s_x[m] = s;
+    }
+
+    // ---- pass 2a: quantise every source element once, into LDS
+    if constexpr (MAXV > 0) {
+#pragma unroll
+        for (int i = 0; i < MAXV; ++i) {
+            const int idx = t + i * LQ_THREADS;
+            if (idx < nvec) {
+                float f[IV::N]; IV::unpack(v[i], f);
+                if constexpr (ES == 1) {
+#pragma unroll
+                    for (int w = 0; w < IV::N / 4; ++w) {
+                        uint32_t p = quant1<OUT>(f[4 * w], r) | (quant1<OUT>(f[4 * w + 1], r) << 8) |
+                                     (quant1<OUT>(f[4 * w + 2], r) << 16) | (quant1<OUT>(f[4 * w + 3], r) << 24);
+                        lds[idx * (IV::N / 4) + w] = p;
+                    }
+                } else {
+#pragma unroll
+                    for (int w = 0; w < IV::N / 2; ++w)
+                        lds[idx * (IV::N / 2) + w] = quant1<OUT>(f[2 * w], r) | (quant1<OUT>(f[2 * w + 1], r) << 16);
+                }
+            }
+        }
+    } else {
+        if constexpr (ES == 1) {
+            uint8_t* l8 = reinterpret_cast<uint8_t*>(lds);
+            for (int k = t; k < K; k += LQ_THREADS) l8[k] = (uint8_t)quant1<OUT>(load_scalar(x + k), r);
+        } else {
+            uint16_t* l16 = reinterpret_cast<uint16_t*>(lds);
+            for (int k = t; k < K; k += LQ_THREADS) l16[k] = (uint16_t)quant1<OUT>(load_scalar(x + k), r);
+        }
+    }
+    __syncthreads();
+
+    // ---- pass 2b: output-oriented gather of the lifted windows (window j reads b = 2N g + 2 l)
+    const int nw1 = N - 1;
+    const int nwin = Kp / 4;
+    uint8_t* out = XL + m * (int64_t)Kp * ES;
+    if constexpr (ES == 1) {
+        if ((Kp & 15) == 0) {
+            for (int c = t; c < nwin / 4; c += LQ_THREADS) {
+                int j = 4 * c, g = j / nw1, l = j - g * nw1;
+                uint32_t w[4];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int b = 2 * N * g + 2 * l;
+                    const uint32_t lo = lds[b >> 2], hi = lds[(b >> 2) + 1];
+                    w[i] = (b & 2) ? ((lo >> 16) | (hi << 16)) : lo;
+                    if (++l == nw1) { l = 0; ++g; }
+                }
+                reinterpret_cast<uint4*>(out)[c] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        } else {
+            for (int j = t; j < nwin; j += LQ_THREADS) {
+                const int g = j / nw1, l = j - g * nw1, b = 2 * N * g + 2 * l;
+                const uint32_t lo = lds[b >> 2], hi = lds[(b >> 2) + 1];
+                reinterpret_cast<uint32_t*>(out)[j] = (b & 2) ? ((lo >> 16) | (hi << 16)) : lo;
+            }
+        }
+    } else {
+        // bf16: a window is 8 bytes = elements b..b+3, b even -> two aligned dwords
+        if ((Kp & 7) == 0) {
+            for (int c = t; c < nwin / 2; c += LQ_THREADS) {
+                int j = 2 * c, g = j / nw1, l = j - g * nw1;
+                uint32_t w[4];
+#pragma unroll
+                for (int i = 0; i < 2; ++i) {
+                    const int b = 2 * N * g + 2 * l;
+                    w[2 * i] = lds[b >> 1]; w[2 * i + 1] = lds[(b >> 1) + 1];
+                    if (++l == nw1) { l = 0; ++g; }
+                }
+                reinterpret_cast<uint4*>(out)[c] = make_uint4(w[0], w[1], w[2], w[3]);
+            }
+        } else {
+            for (int j = t; j < nwin; j += LQ_THREADS) {
+                const int g = j / nw1, l = j - g * nw1, b = 2 * N * g + 2 * l;
+                reinterpret_cast<uint2*>(out)[j] = make_uint2(lds[b >> 1], lds[(b >> 1) + 1]);
+            }
+        }
+    }
+}
+
+template <typename TIN, int OUT>
+static ss_status launch_lift(const void* X, int64_t M, int64_t K, int64_t ldx, int N, void* XL, float* s_x, hipStream_t st)
+{
+    typedef InVec<TIN> IV;
+    const int Kp = (int)lifted_k(K, N);
+    const int ES = OUT == 2 ? 2 : 1;
+    const size_t lds_bytes = (size_t)K * ES + 8;
+    const bool vec_ok = (K % IV::N == 0) && (ldx % IV::N == 0) && (((uintptr_t)X & 15) == 0) && (((uintptr_t)XL & 15) == 0);
+    const int64_t per_thread = (K / IV::N + LQ_THREADS - 1) / LQ_THREADS;
+    dim3 grid((unsigned)M), block(LQ_THREADS);
+    const TIN* x = static_cast<const TIN*>(X);
+    uint8_t* xl = static_cast<uint8_t*>(XL);
+#define SS_LQ(MAXV) hipLaunchKernelGGL((k_act_lift_quant<TIN, OUT, MAXV>), grid, block, lds_bytes, st, x, ldx, (int)K, N, xl, s_x, Kp)
+    if (vec_ok && per_thread <= 4) SS_LQ(4);
+    else if (vec_ok && per_thread <= 10) SS_LQ(10);
+    else if (vec_ok && per_thread <= 20) SS_LQ(20);
+    else SS_LQ(0);
+#undef SS_LQ
+    return launch_status();
+}
+
+// ------------------------------------------------------------------------------------------
+// Offline: magnitude pruning to (2N-2):2N followed by per-output-channel quantisation.
+// One workgroup per weight row; thread per 2N block in the second pass.
+template <typename TIN, int OUT>
+__global__ __launch_bounds__(LQ_THREADS) void k_prune_quant(const TIN* __restrict__ W, int K, int N, uint8_t* __restrict__ Wq,
+                                                             float* __restrict__ s_w)
+{
+    constexpr int ES = OUT == 2 ? 2 : 1;
+    __shared__ float red[LQ_THREADS / 64];
+    const int64_t o = blockIdx.x;
+    const TIN* w = W + o * (int64_t)K;
+    const int t = threadIdx.x;
+    float r = 0.0f;
+    if constexpr (OUT != 2) {
+        float amax = 0.0f;
+        for (int k = t; k < K; k += LQ_THREADS) amax = fmaxf(amax, fabsf(load_scalar(w + k)));
+        amax = block_absmax(amax, red);               // the row maximum always survives pruning
+        constexpr float QMAX = OUT == 0 ? 127.0f : 448.0f;
+        float s = 1.0f;
+        if (amax > 0.0f) { r = QMAX / amax; s = amax / QMAX; }
+        if (t == 0) s_w[o] = s;
+    }
+    const int L = 2 * N, ng = K / L;
+    for (int g = t; g < ng; g += LQ_THREADS) {
+        float v[16];
+#pragma unroll
+        for (int k = 0; k < 16; ++k) v[k] = k < L ? load_scalar(w + g * L + k) : 0.0f;
+        // the two entries dropped are the last two in the order (|w| descending, index ascending)
+        int d1 = 0, d2 = -1;
+        float m1 = fabsf(v[0]);
+#pragma unroll
+        for (int k = 1; k < 16; ++k) if (k < L && fabsf(v[k]) <= m1) { m1 = fabsf(v[k]); d1 = k; }
+        float m2 = 0.0f;
+#pragma unroll
+        for (int k = 0; k < 16; ++k) if (k < L && k != d1 && (d2 < 0 || fabsf(v[k]) <= m2)) { m2 = fabsf(v[k]); d2 = k; }
+#pragma unroll
+        for (int k = 0; k < 16; ++k) {
+            if (k < L) {
+                const uint32_t q = (k == d1 || k == d2) ? 0u : quant1<OUT>(v[k], r);
+                if constexpr (ES == 1) Wq[o * (int64_t)K + g * L + k] = (uint8_t)q;
+                else reinterpret_cast<uint16_t*>(Wq)[o * (int64_t)K + g * L + k] = (uint16_t)q;
+            }
+        }
+    }
+}
+
+}  // namespace ss
+
+using namespace ss;
+
+extern "C" int64_t slide_lifted_k(int64_t K, int N)
+{
+    if (!valid_N(N) || K <= 0 || K % (2 * N) != 0) return -1;
+    return lifted_k(K, N);
+}
+
+extern "C" ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_t K, int64_t ldx, int N,
+                                    ss_dtype out, void* X_lifted, float* s_x, void* stream)
+{
+    if (!valid_N(N)) return SS_ERR_BAD_PATTERN_N;
+    if (M < 0 || K <= 0 || K % (2 * N) != 0 || ldx < K || K > (1 << 24) || M > 0x7FFFFFFF) return SS_ERR_SHAPE;
+    if (in_dtype != SS_IN_F32 && in_dtype != SS_IN_BF16) return SS_ERR_DTYPE;
+    if (out != SS_I8 && out != SS_FP8_E4M3 && out != SS_BF16) return SS_ERR_DTYPE;
+    if ((size_t)K * elem_size(out) + 8 > 64 * 1024) return SS_ERR_SHAPE;    // quantised row must fit in LDS
+    if (M == 0) return SS_OK;
+    if (!X || !X_lifted || (out != SS_BF16 && !s_x)) return SS_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (in_dtype == SS_IN_F32) {
+        if (out == SS_I8) return launch_lift<float, 0>(X, M, K, ldx, N, X_lifted, s_x, st);
+        if (out == SS_FP8_E4M3) return launch_lift<float, 1>(X, M, K, ldx, N, X_lifted, s_x, st);
+        return launch_lift<float, 2>(X, M, K, ldx, N, X_lifted, s_x, st);
+    }
+    if (out == SS_I8) return launch_lift<uint16_t, 0>(X, M, K, ldx, N, X_lifted, s_x, st);
+    if (out == SS_FP8_E4M3) return launch_lift<uint16_t, 1>(X, M, K, ldx, N, X_lifted, s_x, st);
+    return launch_lift<uint16_t, 2>(X, M, K, ldx, N, X_lifted, s_x, st);
+}
+
+template <typename TIN, int OUT>
+static ss_status launch_prune(const void* W, int64_t O, int64_t K, int N, void* Wq, float* s_w, hipStream_t st)
+{
+    hipLaunchKernelGGL((k_prune_quant<TIN, OUT>), dim3((unsigned)O), dim3(LQ_THREADS), 0, st, static_cast<const TIN*>(W), (int)K, N,
+                       static_cast<uint8_t*>(Wq), s_w);
+    return launch_status();
+}
+
+extern "C" ss_status slide_prune_quant(const void* W, ss_act_dtype in_dtype, int64_t O, int64_t K, int N, ss_dtype dtype,
+                                       void* Wq, float* s_w, void* stream)
+{
+    if (!valid_N(N)) return SS_ERR_BAD_PATTERN_N;
+    if (O < 0 || K <= 0 || K % (2 * N) != 0 || K > (1 << 24) || O > 0x7FFFFFFF) return SS_ERR_SHAPE;
+    if (in_dtype != SS_IN_F32 && in_dtype != SS_IN_BF16) return SS_ERR_DTYPE;
+    if (dtype != SS_I8 && dtype != SS_FP8_E4M3 && dtype != SS_BF16) return SS_ERR_DTYPE;
+    if (O == 0) return SS_OK;
+    if (!W || !Wq || (dtype != SS_BF16 && !s_w)) return SS_ERR_NULL;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (in_dtype == SS_IN_F32) {
+        if (dtype == SS_I8) return launch_prune<float, 0>(W, O, K, N, Wq, s_w, st);
+        if (dtype == SS_FP8_E4M3) return launch_prune<float, 1>(W, O, K, N, Wq, s_w, st);
+        return launch_prune<float, 2>(W, O, K, N, Wq, s_w, st);
+    }
+    if (dtype == SS_I8) return launch_prune<uint16_t, 0>(W, O, K, N, Wq, s_w, st);
+    if (dtype == SS_FP8_E4M3) return launch_prune<uint16_t, 1>(W, O, K, N, Wq, s_w, st);
+    return launch_prune<uint16_t, 2>(W, O, K, N, Wq, s_w, st);
+}

@@ -1,0 +1,83 @@
+"""Host-side checks that need no GPU: the shared library loads, exports every symbol the
+header declares, and rejects bad arguments before enqueuing anything."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2603_05232_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2603_05232_amd.build import build
+        build()
+    return binding.load()
+
+
+def test_header_symbols_are_exported(lib):
+    with open(os.path.join(ROOT, "include", "slidesparse.h")) as f:
+        text = re.sub(r"/\*.*?\*/", "", f.read(), flags=re.S)
+    declared = set(re.findall(r"\b(\w+)\s*\([^;{]*\)\s*;", text))
+    declared -= {"defined"}
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_lifted_k(lib):
+    assert binding.slide_lifted_k(512, 4) == 768
+    assert binding.slide_lifted_k(3584, 4) == 5376
+    assert binding.slide_lifted_k(6144, 3) == 8192
+    assert binding.slide_lifted_k(5120, 5) == 8192
+    assert binding.slide_lifted_k(64, 2) == 64
+    assert binding.slide_lifted_k(100, 4) == -1
+    assert binding.slide_lifted_k(64, 1) == -1 and binding.slide_lifted_k(64, 9) == -1
+    assert binding.slide_lifted_k(0, 4) == -1
+
+
+def test_packed_sizes(lib):
+    v, m = binding.slide_packed_sizes(512, 512, 4, "i8")
+    assert (v, m) == (512 * 384, 512 * 96)
+    v, m = binding.slide_packed_sizes(37888, 3584, 4, "i8")
+    assert v + m == int(0.9375 * 37888 * 3584)            # values 0.75x + index 0.1875x of dense bytes
+    v, m = binding.slide_packed_sizes(130, 512, 4, "i8")    # rows padded to a multiple of 128
+    assert v == 256 * 384
+    with pytest.raises(binding.SlideSparseError) as e:
+        binding.slide_packed_sizes(512, 520, 4, "i8")       # K' = 780 is not a multiple of 128
+    assert e.value.code == 3
+
+
+def test_argument_errors_return_codes(lib):
+    vp = ctypes.c_void_p
+    one = ctypes.c_void_p(16)                               # non-null, never dereferenced: validation fails first
+    # bad N
+    assert lib.act_lift_quant(one, 0, 4, 64, 64, 1, 0, one, one, None) == 2
+    assert lib.slide_decompose(one, 4, 64, 9, 0, one, one, None, None) == 2
+    # K not a multiple of 2N, ldx < K
+    assert lib.act_lift_quant(one, 0, 4, 60, 60, 4, 0, one, one, None) == 3
+    assert lib.act_lift_quant(one, 0, 4, 64, 32, 4, 0, one, one, None) == 3
+    # bad dtypes
+    assert lib.act_lift_quant(one, 7, 4, 64, 64, 4, 0, one, one, None) == 4
+    assert lib.act_lift_quant(one, 0, 4, 64, 64, 4, 5, one, one, None) == 4
+    # null pointers
+    assert lib.act_lift_quant(None, 0, 4, 64, 64, 4, 0, one, one, None) == 1
+    assert lib.act_lift_quant(one, 0, 4, 64, 64, 4, 0, one, None, None) == 1
+    assert lib.slide_prune_quant(None, 0, 4, 64, 4, 0, one, one, None) == 1
+    assert lib.slide_decompose(None, 128, 512, 4, 0, one, one, None, None) == 1
+    assert lib.slide_decompose_canonical(one, 4, 64, 4, 0, None, one, None, None) == 1
+    # GEMMs: K' must be a multiple of 128, ldy >= O, pointers non-null and 16-byte aligned
+    assert lib.slide_sparse_gemm(one, one, one, one, one, 16, 128, 100, 0, one, 128, None) == 3
+    assert lib.dense_gemm(one, one, one, one, 16, 128, 128, 0, one, 64, None) == 3
+    assert lib.dense_gemm(None, one, one, one, 16, 128, 128, 0, one, 128, None) == 1
+    assert lib.dense_gemm(ctypes.c_void_p(8), one, one, one, 16, 128, 128, 0, one, 128, None) == 3
+    assert lib.dense_gemm(one, one, one, one, 16, 128, 128, 9, one, 128, None) == 4
+    # empty problems are fine and touch nothing
+    assert lib.act_lift_quant(None, 0, 0, 64, 64, 4, 0, None, None, None) == 0
+    assert lib.dense_gemm(None, None, None, None, 0, 128, 128, 0, None, 128, None) == 0
+    assert binding.status_string(0) == "ok" and "N" in binding.status_string(2)
+    assert lib.slide_format_version() >= 1

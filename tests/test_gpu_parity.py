@@ -1,0 +1,189 @@
+"""GPU parity: every C-ABI entry point against the CPU oracle on the same seeded inputs.
+Integer / byte / index results must be bit-exact."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slide_oracle as so
+from oracle import gemm_ref
+from paper_2603_05232_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def host(t):
+    torch.cuda.synchronize()
+    return t.cpu().numpy()
+
+
+def bits16(t):
+    return host(t.view(torch.int16)).view(np.uint16)
+
+
+def to_dev_q(q, dtype):
+    """oracle storage array -> torch tensor of the binding's storage dtype"""
+    if dtype == "i8":
+        return dev(q.astype(np.int8))
+    if dtype == "fp8":
+        return dev(q.astype(np.uint8))
+    return dev(q.astype(np.uint16).view(np.int16)).view(torch.bfloat16)
+
+
+def from_dev_q(t, dtype):
+    if dtype == "bf16":
+        return bits16(t)
+    return host(t)
+
+
+# ------------------------------------------------------------------ act_lift_quant
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("N,M,K", [(4, 16, 512), (2, 7, 64), (3, 5, 6 * 37), (4, 33, 3584), (5, 3, 5120), (8, 4, 16 * 9),
+                                   (4, 2, 18944), (3, 9, 6144), (4, 3, 8 * 3001)])
+def test_act_lift_quant_fp32(dtype, N, M, K):
+    X = synth.activations(M, K, seed=N * 100 + M, n_outliers=min(4, K // 8))
+    if M > 2:
+        X[1] = 0.0                                           # an all-zero token
+        X[2, K // 2] = -3.0 * np.abs(X[2]).max()              # negative extreme
+    exp, s = so.act_lift_quant(X, N, dtype)
+    got, gs = binding.act_lift_quant(dev(X), N, dtype)
+    assert tuple(got.shape) == exp.shape
+    assert np.array_equal(from_dev_q(got, dtype), exp)
+    if dtype == "bf16":
+        assert gs is None
+    else:
+        assert np.array_equal(host(gs), s)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+def test_act_lift_quant_bf16_input_and_row_stride(dtype):
+    M, K, N = 19, 1024, 4
+    Xf = synth.activations(M, K, seed=5)
+    Xb = so.bf16_bits(Xf)                                    # bf16 input tensor, exact fp32 value of it for the oracle
+    exp, s = so.act_lift_quant(so.bf16_to_f32(Xb), N, dtype)
+    xt = dev(Xb.view(np.int16)).view(torch.bfloat16)
+    got, gs = binding.act_lift_quant(xt, N, dtype)
+    assert np.array_equal(from_dev_q(got, dtype), exp)
+    if dtype != "bf16":
+        assert np.array_equal(host(gs), s)
+    # strided rows (a column slice of a wider matrix), fp32
+    wide = np.zeros((M, K + 64), dtype=np.float32)
+    wide[:, 32:32 + K] = Xf
+    exp2, s2 = so.act_lift_quant(Xf, N, dtype)
+    got2, gs2 = binding.act_lift_quant(dev(wide)[:, 32:32 + K], N, dtype)
+    assert np.array_equal(from_dev_q(got2, dtype), exp2)
+
+
+# ------------------------------------------------------------------ slide_prune_quant
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("N,O,K", [(4, 512, 512), (2, 9, 64), (3, 17, 6 * 50), (5, 6, 5120), (8, 5, 16 * 11)])
+def test_prune_quant(dtype, N, O, K):
+    W = synth.weights(O, K, seed=N)
+    W[0, : 2 * N] = 0.5                                       # ties: the lower indices survive
+    if O > 3:
+        W[3] = 0.0
+    expq, exps = so.prepare_weights(W, N, dtype)
+    gq, gs = binding.slide_prune_quant(dev(W), N, dtype)
+    assert np.array_equal(from_dev_q(gq, dtype), expq)
+    if dtype != "bf16":
+        assert np.array_equal(host(gs), exps)
+
+
+# ------------------------------------------------------------------ slide_decompose (canonical form)
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("N,O,K", [(4, 512, 512), (2, 5, 64), (3, 33, 6 * 21), (5, 7, 200), (6, 3, 120), (7, 2, 14 * 5), (8, 4, 160)])
+def test_decompose_canonical(dtype, N, O, K):
+    W = synth.weights(O, K, seed=10 + N)
+    Wq, _ = so.prepare_weights(W, N, dtype)
+    rng = np.random.default_rng(N)
+    Wq = Wq.copy()
+    Wq[rng.random(Wq.shape) < 0.15] = 0                       # blocks with fewer than 2N-2 non-zeros
+    if dtype != "i8":
+        neg0 = 0x80 if dtype == "fp8" else 0x8000
+        Wq[rng.random(Wq.shape) < 0.05] = neg0               # -0 must count as zero
+    Wp = so.slide_decompose(Wq, N, dtype)
+    ev, ei = so.compress_24(Wp, dtype)
+    gv, gi, viol = binding.slide_decompose_canonical(to_dev_q(Wq, dtype), N, dtype)
+    gv, gi = from_dev_q(gv, dtype), host(gi)
+    assert int(host(viol)[0]) == 0
+    assert np.all((gi & 3) < ((gi >> 2) & 3)) and np.all(gi < 16)
+    # what is unique: the densified windows; -0 inputs never surface as stored values
+    dense = so.decompress_24(gv, gi)
+    assert np.array_equal(~so.is_zero(dense, dtype), ~so.is_zero(Wp, dtype))
+    assert np.array_equal(np.where(so.is_zero(dense, dtype), 0, dense), Wp)
+    # and this library follows the same padding rule as the oracle's canonical form
+    assert np.array_equal(gi, ei)
+    assert np.array_equal(np.where(so.is_zero(gv, dtype), 0, gv), ev)
+
+
+def test_decompose_counts_pattern_violations():
+    N, O, K = 4, 4, 64
+    Wq = np.zeros((O, K), dtype=np.int8)
+    Wq[1, 8:15] = 1                                          # 7 non-zeros in one 6:8 block
+    Wq[2, 0:8] = 2                                           # 8 non-zeros
+    Wq[3, 16:22] = 3                                         # 6: allowed
+    _, _, viol = binding.slide_decompose_canonical(dev(Wq), N, "i8")
+    assert int(host(viol)[0]) == 2
+
+
+# ------------------------------------------------------------------ GEMMs
+def _gemm_case(M, O, K, N, seed):
+    X = synth.activations(M, K, seed)
+    W = synth.weights(O, K, seed)
+    ref = so.linear_reference(X, W, N, "i8")
+    return X, W, ref
+
+
+def _acc_big(Xq, Wq):
+    return gemm_ref.gemm_i8_i64(Xq, Wq)
+
+
+@pytest.mark.parametrize("N,M,O,K", [(4, 16, 512, 512),          # the anchor case
+                                     (4, 300, 640, 1024),        # several tiles, ragged tokens and channels
+                                     (3, 257, 130, 768),         # K' = 1024, one ragged panel
+                                     (5, 64, 256, 640),          # K' = 1024
+                                     (2, 40, 128, 256),          # native 2:4
+                                     (4, 1, 384, 512)])          # a single token
+def test_sparse_and_dense_gemm_int8(N, M, O, K):
+    X, W, ref = _gemm_case(M, O, K, N, seed=M + O)
+    Xd, Wd = dev(X), dev(W)
+    Wq, s_w = binding.slide_prune_quant(Wd, N, "i8")
+    assert np.array_equal(host(Wq), ref["Wq"]) and np.array_equal(host(s_w), ref["s_w"])
+    w_vals, w_meta, viol = binding.slide_decompose(Wq, N, "i8", count_violations=True)
+    XL, s_x = binding.act_lift_quant(Xd, N, "i8")
+    Y = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, "i8")
+    assert int(host(viol)[0]) == 0
+    assert np.array_equal(bits16(Y), ref["Y"])
+    # dense baseline at the original K (N = 2 lifting is plain quantisation)
+    Xq, s_x2 = binding.act_lift_quant(Xd, 2, "i8")
+    assert np.array_equal(host(Xq), ref["Xq"]) and np.array_equal(host(s_x2), ref["s_x"])
+    Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, "i8")
+    assert np.array_equal(bits16(Yd), ref["Y"])
+
+
+def test_gemm_strided_output_and_random_sparse_weights():
+    # weights that are not the product of pruning: random values with random (<= 6 of 8) supports,
+    # so windows with 0, 1 and 2 stored values all occur; output written into a wider buffer
+    rng = np.random.default_rng(77)
+    M, O, K, N = 70, 256, 512, 4
+    Wq = rng.integers(-127, 128, size=(O, K)).astype(np.int8)
+    keep = np.argsort(rng.random((O, K // 8, 8)), axis=-1) < rng.integers(0, 7, size=(O, K // 8, 1))
+    Wq = (Wq.reshape(O, K // 8, 8) * keep).reshape(O, K).astype(np.int8)
+    Xq = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    s_x = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    s_w = rng.uniform(1e-4, 1e-3, O).astype(np.float32)
+    exp = so.epilogue(so.gemm_exact(Xq, Wq, "i8"), s_x, s_w, "i8")
+    w_vals, w_meta = binding.slide_decompose(dev(Wq), N, "i8")
+    XL = dev(so.lift(Xq, N))
+    buf = torch.full((M, O + 64), -1.0, dtype=torch.bfloat16, device=DEV)
+    binding.slide_sparse_gemm(XL, dev(s_x), w_vals, w_meta, dev(s_w), O, "i8", out=buf[:, :O])
+    assert np.array_equal(bits16(buf[:, :O].contiguous()), exp)
+    assert torch.all(buf[:, O:] == -1.0)
+    buf2 = torch.full((M, O + 64), -1.0, dtype=torch.bfloat16, device=DEV)
+    binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8", out=buf2[:, :O])
+    assert np.array_equal(bits16(buf2[:, :O].contiguous()), exp)
+    assert torch.all(buf2[:, O:] == -1.0)
