@@ -97,7 +97,7 @@ __global__ __launch_bounds__(256) void k_decompose_packed8(const uint8_t* __rest
         if (violations && bad) atomicAdd(violations, bad);
     }
     vals[slot] = make_uint4(v[0], v[1], v[2], v[3]);
-    meta[slot] = m;
+    meta[(ps * 64 + lane) * FRAGS_PER_PANEL + f] = m;   // index words lane-major: one 16-byte read gives a lane all four
 }
 
 }  // namespace ss

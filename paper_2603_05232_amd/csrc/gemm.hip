@@ -1,279 +1,477 @@
 // slide_sparse_gemm and dense_gemm for gfx950.
 //
-// Both kernels share one tile engine: a 512-thread workgroup (8 wavefronts, two per SIMD)
-// owns a 256 (output channels) x 256 (tokens) tile of Y; wavefront (wo, wt) accumulates the
-// 128 x 64 sub-tile [wo*128, +128) x [wt*64, +64) as 4 x 2 32x32 matrix-instruction blocks.
-// Operand tiles stream HBM/L2 -> LDS with direct-to-LDS 16-byte loads through a ring of
-// stages, so no registers are spent on data in flight; LDS rows are XOR-swizzled at 16-byte
-// granularity (applied on the global-address side of the direct loads) so that the 32 lanes
-// of a matrix-operand read hit all 64 banks.  The weights are the A operand (sparse for
-// slide_sparse_gemm: v_smfmac_i32_32x32x64_i8 consumes 16 stored bytes + one index word per
-// lane), tokens are the B operand, and the accumulator D[channel][token] leaves each lane
-// with 64 consecutive output channels of one token, stored as full 128-byte lines.
+// Tile engine shared by both kernels: a persistent 512-thread workgroup (8 wavefronts, two per SIMD)
+// owns a 256 (output channels) x 256 (tokens) tile of Y at a time; wavefront (wo, wt) accumulates the
+// 128 x 64 sub-tile [wo*128, +128) x [wt*64, +64) as 4 x 2 blocks of a 32x32 matrix instruction.  The
+// weights are the A operand (sparse for slide_sparse_gemm: v_smfmac_i32_32x32x64_i8 takes 16 stored
+// bytes + one index word per lane), tokens are the B operand.
+//
+// Data movement.  Operand tiles go HBM/L2 -> LDS with direct-to-LDS loads (no registers hold data in
+// flight) into rings of units; token rows are fetched as whole 128-byte lines and XOR-swizzled at
+// 16-byte granularity (applied on the global-address side, because a direct load writes
+// lane-contiguous LDS) so the 32 lanes of an operand read hit all 64 banks.
+//
+// Schedule.  The k loop advances in sub-steps of one matrix-instruction depth (64 lifted columns
+// sparse, 32 columns dense).  Every wavefront alternates a read phase (wait for its landed loads,
+// request new units, fetch the operand registers of its next sub-step from LDS) and a matrix phase
+// (eight back-to-back matrix instructions), separated by workgroup barriers.  The two wavefronts that
+// share a SIMD run half a sub-step apart, so while one issues matrix instructions the other does its
+// memory work and the matrix pipe always has a feeder.
+//
+// Epilogue.  D[channel][token] leaves each lane with 64 consecutive output channels of one token; the
+// scaled bf16 values are staged through the (then idle) LDS so that every global store instruction
+// writes whole 256-byte row segments.
 #include "ss_common.h"
 #include "packed_layout.h"
+#include <cstdlib>
+
 
 namespace ss {
 
-constexpr int G_THREADS = 512;
+constexpr int G_WAVES = 8;
+constexpr int G_THREADS = 64 * G_WAVES;
+constexpr int NBF = 2;    // 32-token B fragments per wavefront (4 x 2 accumulator blocks of 32 x 32)
 constexpr int BO = 256;   // output channels per workgroup
 constexpr int BT = 256;   // tokens per workgroup
+constexpr int ROWB = 128; // bytes of one LDS row of a row-major operand tile (one cache line)
 
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
 
+// 16 (or 4) bytes per lane, global -> LDS; the LDS address is wave-uniform base + lane * size
 __device__ inline void lds_dma16(const void* g, void* lds_wave_base)
 {
-    // 16 bytes per lane, global -> LDS; the LDS address is wave-uniform base + lane * 16
     __builtin_amdgcn_global_load_lds((gbl_void*)g, (lds_void*)lds_wave_base, 16, 0, 0);
 }
+__device__ inline void lds_dma4(const void* g, void* lds_wave_base)
+{
+    __builtin_amdgcn_global_load_lds((gbl_void*)g, (lds_void*)lds_wave_base, 4, 0, 0);
+}
 
+// Wait until at most N of this wave's direct loads are still in flight and all of its LDS reads
+// have returned (gfx9 s_waitcnt encoding: vmcnt = bits [3:0] and [15:14], lgkmcnt = bits [11:8]).
 template <int N> __device__ inline void wait_vmcnt()
 {
-    // gfx9 s_waitcnt encoding: vmcnt = bits [3:0] and [15:14]; leave expcnt / lgkmcnt at "no wait"
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0xF << 8));
-}
-
-// Workgroup barrier without the memory fence of __syncthreads(): the direct-to-LDS loads still in
-// flight for later stages must stay in flight.  The empty asm statements keep the compiler from
-// moving LDS reads or load issues across it.
-__device__ inline void stage_barrier()
-{
     asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();     // stage kt has landed for every wave; stage kt-1 is no longer being read
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
     asm volatile("" ::: "memory");
 }
 
-// XCD-aware tile order: consecutive workgroup ids go round-robin to the 8 XCDs, so give each
-// XCD one contiguous range of tiles, and order tiles in bands of 8 token tiles so the 32
-// workgroups resident on an XCD share weight panels and token tiles in its L2.
-__device__ inline void tile_of_block(int tiles_o, int tiles_t, int& to, int& tt)
+// all LDS reads of this wave have returned (loads in flight are left alone)
+__device__ inline void wait_lgkm0()
 {
-    const int nb = gridDim.x, bid = blockIdx.x;
-    const int xcd = bid & 7, idx = bid >> 3;
-    const int q = nb >> 3, rem = nb & 7;
-    const int tile = xcd * q + (xcd < rem ? xcd : rem) + idx;
-    constexpr int BAND = 8;
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8));
+    asm volatile("" ::: "memory");
+}
+
+// Workgroup barrier without the memory fence of __syncthreads(): direct-to-LDS loads in flight
+// for later units must stay in flight.  The empty asm statements keep the compiler from moving
+// LDS accesses or load issues across it.
+__device__ inline void wg_barrier()
+{
+    asm volatile("" ::: "memory");
+    __builtin_amdgcn_s_barrier();
+    asm volatile("" ::: "memory");
+}
+
+// Persistent workgroups: the grid holds one workgroup per compute unit and workgroup b processes
+// tiles b, b + grid, b + 2 grid, ...  Workgroup ids go round-robin to the 8 XCDs, so within a full
+// round each XCD is given one contiguous run of tiles, and tiles are ordered in bands of 8 token
+// tiles so that the 32 workgroups resident on an XCD share weight panels and token tiles in its L2.
+__device__ inline bool tile_of_round(int round, int tiles_o, int tiles_t, int& to, int& tt)
+{
+    const int nb = gridDim.x, bid = blockIdx.x, total = tiles_o * tiles_t;
+    const int base = round * nb;
+    if (base + bid >= total) return false;
+    int tile = base + bid;
+    if (base + nb <= total && (nb & 7) == 0) tile = base + (bid & 7) * (nb >> 3) + (bid >> 3);
+#ifndef SS_BAND
+#define SS_BAND 8
+#endif
+    constexpr int BAND = SS_BAND;
     const int per_band = BAND * tiles_o;
     const int band = tile / per_band, within = tile - band * per_band;
     const int bw = min(BAND, tiles_t - band * BAND);
     to = within / bw;
     tt = band * BAND + (within - to * bw);
+    return true;
 }
 
-// ---- LDS tile of a row-major 8-bit operand: ROWS rows x KT bytes, XOR-swizzled -------------
-template <int KT> __device__ inline int swz(int row) { return (row / (16 / (KT / 16))) % (KT / 16); }
+// ---- LDS tile of a row-major 8-bit operand: 256 rows x 128 bytes, XOR-swizzled -----------------
+__device__ inline int swz(int row) { return (row >> 1) & 7; }
 
-// issue the direct-to-LDS loads of a [256 x KT] tile; rows >= nrows are clamped (their
-// products are never stored)
-template <int KT>
-__device__ inline void load_rows_tile(const uint8_t* __restrict__ base, int64_t ld, int64_t row0, int64_t nrows, int64_t k0, uint8_t* lds_tile)
-{
-    constexpr int CPR = KT / 16;                 // 16-byte chunks per row
-    constexpr int RPI = 64 / CPR;                // rows per wavefront-wide load
-    constexpr int NI = 256 / (RPI * (G_THREADS / 64));
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+// per-thread source pointers (k offset 0) of the direct loads that fill a [256 x 128 B] tile; rows
+// beyond nrows are clamped (their products are never stored)
+constexpr int ROW_LOADS = 256 / (8 * G_WAVES);      // 8 rows per wavefront-wide load
+struct RowTileLoader {
+    const uint8_t* base;                            // first row of the tile (wave-uniform, lives in SGPRs)
+    uint32_t off[ROW_LOADS];                        // this lane's byte offset from it, per load
+    __device__ void init(const uint8_t* mat, int64_t ld, int64_t row0, int64_t nrows, int wave, int lane)
+    {
+        base = mat + row0 * ld;
 #pragma unroll
-    for (int i = 0; i < NI; ++i) {
-        const int r0 = (i * (G_THREADS / 64) + wave) * RPI;
-        const int row = r0 + lane / CPR;
-        const int lc = (lane % CPR) ^ swz<KT>(row);
-        int64_t grow = row0 + row;
-        grow = grow < nrows ? grow : nrows - 1;
-        lds_dma16(base + grow * ld + k0 + lc * 16, lds_tile + r0 * KT);
+        for (int i = 0; i < ROW_LOADS; ++i) {
+            const int row = (i * G_WAVES + wave) * 8 + (lane >> 3);
+            const int lc = (lane & 7) ^ swz(row);
+            int64_t grow = row0 + row;
+            grow = grow < nrows ? grow : nrows - 1;
+            off[i] = (uint32_t)((grow - row0) * ld) + lc * 16;
+        }
     }
-}
+    __device__ void issue(int64_t k0, uint8_t* lds_tile, int wave) const
+    {
+        const uint8_t* b = base + k0;
+#pragma unroll
+        for (int i = 0; i < ROW_LOADS; ++i) lds_dma16(b + off[i], lds_tile + (i * G_WAVES + wave) * 8 * ROWB);
+    }
+};
 
-template <int KT> __device__ inline const v4i* tile_chunk(const uint8_t* lds_tile, int row, int lc)
+__device__ inline const v4i* tile_chunk(const uint8_t* lds_tile, int row, int lc)
 {
-    return reinterpret_cast<const v4i*>(lds_tile + row * KT + ((lc ^ swz<KT>(row)) << 4));
+    return reinterpret_cast<const v4i*>(lds_tile + row * ROWB + ((lc ^ swz(row)) << 4));
 }
 
-// ---- epilogue: Y = bf16((float(acc) * s_x) * s_w), 64 consecutive channels per lane ---------
-__device__ inline uint32_t pack_bf16x2(float a, float b) { return (uint32_t)f32_to_bf16_bits(a) | ((uint32_t)f32_to_bf16_bits(b) << 16); }
+// ---- epilogue: Y = bf16((float(acc) * s_x) * s_w), staged through LDS for coalesced stores ------
+// two fp32 -> packed bf16 (round to nearest even) in one v_cvt_pk_bf16_f32
+__device__ inline uint32_t pack_bf16x2(float a, float b)
+{
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    typedef float f32x2 __attribute__((ext_vector_type(2)));
+    const f32x2 v = {a, b};
+    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
+}
 
+constexpr int EP_ROWB = 272;                        // 128 channels x 2 B + 16 B pad (bank spread)
+constexpr int EP_TILE_BYTES = 256 * 2 * EP_ROWB;    // 256 tokens x 2 channel panels
+
+// acc[f][b][r] of lane (n = lane & 31, h = lane >> 5) is channel o_base + 64 h + 16 f + r of token
+// t_base + 32 b + n.  `stage` is this wavefront's private 32 NBF rows of EP_ROWB bytes of LDS.
 template <typename ACC>
-__device__ inline void store_tile(const ACC (&acc)[4][2], const float* __restrict__ s_x, const float* __restrict__ s_w, uint16_t* __restrict__ Y,
-                                  int64_t ldy, int64_t M, int64_t O, int64_t o_base, int64_t t_base)
+__device__ inline void store_tile(const ACC (&acc)[4][NBF], const float* __restrict__ s_x, const float* __restrict__ s_w, uint16_t* __restrict__ Y,
+                                  int64_t ldy, int64_t M, int64_t O, int64_t o_base, int64_t t_base, uint8_t* stage)
 {
     const int lane = threadIdx.x & 63, n = lane & 31, h = lane >> 5;
     const int64_t o0 = o_base + 64 * h;
-    const bool fast = (o0 + 64 <= O) && ((ldy & 7) == 0) && (((uintptr_t)Y & 15) == 0);
+    const bool sw_vec = (o0 + 64 <= O) && (((uintptr_t)s_w & 15) == 0);
 #pragma unroll
-    for (int b = 0; b < 2; ++b) {
-        const int64_t tok = t_base + b * 32 + n;
-        if (tok >= M) continue;
-        const float sx = s_x[tok];
-        uint16_t* yrow = Y + tok * ldy + o0;
+    for (int f = 0; f < 4; ++f) {
+        float sw[16];
+        if (sw_vec) {
 #pragma unroll
-        for (int f = 0; f < 4; ++f) {
-            if (fast) {
-                const float4* sw4 = reinterpret_cast<const float4*>(s_w + o0 + 16 * f);
-                uint32_t w[8];
+            for (int i = 0; i < 4; ++i) {
+                const float4 v = reinterpret_cast<const float4*>(s_w + o0 + 16 * f)[i];
+                sw[4 * i] = v.x; sw[4 * i + 1] = v.y; sw[4 * i + 2] = v.z; sw[4 * i + 3] = v.w;
+            }
+        } else {
 #pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const float4 sw = sw4[q];
-                    w[2 * q] = pack_bf16x2(((float)acc[f][b][4 * q] * sx) * sw.x, ((float)acc[f][b][4 * q + 1] * sx) * sw.y);
-                    w[2 * q + 1] = pack_bf16x2(((float)acc[f][b][4 * q + 2] * sx) * sw.z, ((float)acc[f][b][4 * q + 3] * sx) * sw.w);
-                }
-                uint4* dst = reinterpret_cast<uint4*>(yrow + 16 * f);
-                dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-                dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+            for (int i = 0; i < 16; ++i) { const int64_t o = o0 + 16 * f + i; sw[i] = s_w[o < O ? o : O - 1]; }
+        }
+#pragma unroll
+        for (int b = 0; b < NBF; ++b) {
+            const int64_t tok = t_base + b * 32 + n;
+            const float sx = s_x[tok < M ? tok : M - 1];
+            uint32_t w[8];
+#pragma unroll
+            for (int q = 0; q < 8; ++q)
+                w[q] = pack_bf16x2(((float)acc[f][b][2 * q] * sx) * sw[2 * q], ((float)acc[f][b][2 * q + 1] * sx) * sw[2 * q + 1]);
+            uint4* dst = reinterpret_cast<uint4*>(stage + (b * 32 + n) * EP_ROWB + h * 128 + 32 * f);
+            dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
+            dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+        }
+    }
+    // wavefront-private staging: its own LDS writes only need to have completed
+    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+    const bool vec_ok = ((ldy & 7) == 0) && (((uintptr_t)Y & 15) == 0) && ((o_base & 7) == 0);
+    const int seg = lane & 15;                      // 16-byte segment (8 channels) of the 256-byte row
+    const int64_t o = o_base + 8 * seg;
+#pragma unroll 8
+    for (int i = 0; i < 8 * NBF; ++i) {
+        const int r = 4 * i + (lane >> 4);
+        const int64_t tok = t_base + r;
+        const uint4 v = *reinterpret_cast<const uint4*>(stage + r * EP_ROWB + seg * 16);
+        if (tok < M) {
+            uint16_t* dst = Y + tok * ldy + o;
+            if (vec_ok && o + 8 <= O) {
+                // Y is written once and not read again by this kernel: stream it past the caches
+                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                __builtin_nontemporal_store((u32x4){v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(dst));
             } else {
+                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    const int64_t o = o0 + 16 * f + r;
-                    if (o < O) yrow[16 * f + r] = f32_to_bf16_bits(((float)acc[f][b][r] * sx) * s_w[o]);
-                }
+                for (int e = 0; e < 8; ++e)
+                    if (o + e < O) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
             }
         }
     }
 }
 
-// ---- dense INT8: Y = Xq . Wq^T ----------------------------------------------------------------
-constexpr int D_KT = 64, D_STAGES = 4, D_STAGE_BYTES = (BO + BT) * D_KT;
+template <typename ACC> __device__ inline void zero_acc(ACC (&acc)[4][NBF])
+{
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+        for (int b = 0; b < NBF; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) acc[f][b][r] = 0;
+}
 
+// debug variants that skip the epilogue still have to consume the accumulators
+template <typename ACC> __device__ inline void keep_alive(const ACC (&acc)[4][NBF], uint16_t* Y)
+{
+    int sum = 0;
+#pragma unroll
+    for (int f = 0; f < 4; ++f)
+#pragma unroll
+        for (int b = 0; b < NBF; ++b)
+#pragma unroll
+            for (int r = 0; r < 16; ++r) sum += (int)acc[f][b][r];
+    if (sum == 0x7fffffff) Y[0] = 1;
+}
+
+// Phase groups: wavefronts w and w + 4 of a workgroup share a SIMD (checked on the device), so the two
+// groups that run half a sub-step apart are waves {0..3} and {4..7}: grp = wave >> 2.
+
+// ---- dense INT8: Y = Xq . Wq^T -------------------------------------------------------------------
+// Units of 128 k-bytes (4 sub-steps of the 32x32x32 instruction); rings of two units per operand.
+constexpr int D_UNIT = BO * ROWB;                   // 32 KB, same for A and B
+constexpr int D_LDS = EP_TILE_BYTES > 4 * D_UNIT ? EP_TILE_BYTES : 4 * D_UNIT;   // rings 128 KB; staging 136 KB
+
+struct DenseFrags { v4i a[4]; v4i b[NBF]; };
+
+template <int DBG>
 __global__ __launch_bounds__(G_THREADS) void k_dense_i8(const uint8_t* __restrict__ Xq, const float* __restrict__ s_x, const uint8_t* __restrict__ Wq,
                                                         const float* __restrict__ s_w, int64_t M, int64_t O, int64_t K, uint16_t* __restrict__ Y,
                                                         int64_t ldy, int tiles_o, int tiles_t)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-    int to, tt;
-    tile_of_block(tiles_o, tiles_t, to, tt);
-    const int64_t o_blk = (int64_t)to * BO, t_blk = (int64_t)tt * BT;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int wo = wave & 1, wt = wave >> 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR
+    const int wo = wave & 1, wt = wave >> 1, grp = wave >> 2;
     const int row = lane & 31, q = lane >> 5;
-    const int nk = (int)(K / D_KT);
-    constexpr int LPS = 2 * (256 / ((64 / (D_KT / 16)) * (G_THREADS / 64)));   // loads per thread per stage
+    const int nunits = (int)(K / ROWB);
+    const int S = 4 * nunits;
+    int arow[4], brow[NBF];
+#pragma unroll
+    for (int f = 0; f < 4; ++f) arow[f] = wo * 128 + panel_row(f, row);
+#pragma unroll
+    for (int bb = 0; bb < NBF; ++bb) brow[bb] = wt * (32 * NBF) + bb * 32 + row;
 
-    v16i acc[4][2];
+    int to, tt;
+    for (int round = 0; tile_of_round(round, tiles_o, tiles_t, to, tt); ++round) {
+        const int64_t o_blk = (int64_t)to * BO, t_blk = (int64_t)tt * BT;
+        RowTileLoader la, lb;
+        la.init(Wq, K, o_blk, O, wave, lane);
+        lb.init(Xq, K, t_blk, M, wave, lane);
+        auto issue = [&](int unit) {
+            if constexpr (!(DBG & 1)) {
+                la.issue((int64_t)unit * ROWB, smem + (unit & 1) * D_UNIT, wave);
+                lb.issue((int64_t)unit * ROWB, smem + 2 * D_UNIT + (unit & 1) * D_UNIT, wave);
+            }
+        };
+        v16i acc[4][NBF];
+        zero_acc(acc);
+        DenseFrags R0, R1;
+        auto read_frags = [&](DenseFrags& R, int t) {
+            if constexpr (!(DBG & 2)) {
+                const uint8_t* sa = smem + ((t >> 2) & 1) * D_UNIT;
+                const uint8_t* sb = sa + 2 * D_UNIT;
+                const int lc = 2 * (t & 3) + q;
 #pragma unroll
-    for (int f = 0; f < 4; ++f)
+                for (int f = 0; f < 4; ++f) R.a[f] = *tile_chunk(sa, arow[f], lc);
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+                for (int bb = 0; bb < NBF; ++bb) R.b[bb] = *tile_chunk(sb, brow[bb], lc);
+            }
+        };
+        // matrix phase of sub-step t: first put the operand reads of sub-step t+1 in flight, then issue the
+        // eight matrix instructions of sub-step t
+        auto matrix_phase = [&](const DenseFrags& cur, DenseFrags& nxt, int t) {
+            if (t + 1 < S) read_frags(nxt, t + 1);
+            if constexpr (!(DBG & 2)) {
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int r = 0; r < 16; ++r) acc[f][b][r] = 0;
+                for (int f = 0; f < 4; ++f)
+#pragma unroll
+                    for (int bb = 0; bb < NBF; ++bb) acc[f][bb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[f], cur.b[bb], acc[f][bb], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            wait_lgkm0();                                 // the reads of t+1 have returned before the next barrier
+        };
+        // memory phase number xi of this wavefront (its partner on the SIMD is in a matrix phase).  Unit
+        // j = sub-steps 4j..4j+3: it is awaited at xi = 4j - 2 and, once its ring slot is free, the unit two
+        // ahead is requested at xi = 4j + 3.
+        auto memory_phase = [&](int xi) {
+            if ((xi & 3) == 2 && ((xi + 2) >> 2) < nunits) wait_vmcnt<0>();
+            if ((xi & 3) == 3 && ((xi + 1) >> 2) + 1 < nunits) issue(((xi + 1) >> 2) + 1);
+        };
 
-    auto issue = [&](int kt) {
-        uint8_t* st = smem + (kt % D_STAGES) * D_STAGE_BYTES;
-        load_rows_tile<D_KT>(Wq, K, o_blk, O, (int64_t)kt * D_KT, st);
-        load_rows_tile<D_KT>(Xq, K, t_blk, M, (int64_t)kt * D_KT, st + BO * D_KT);
-    };
-#pragma unroll
-    for (int s = 0; s < D_STAGES - 1; ++s) if (s < nk) issue(s);
-
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + D_STAGES - 2 < nk) wait_vmcnt<(D_STAGES - 2) * LPS>(); else wait_vmcnt<0>();
-        stage_barrier();
-        if (kt + D_STAGES - 1 < nk) issue(kt + D_STAGES - 1);
-        const uint8_t* sa = smem + (kt % D_STAGES) * D_STAGE_BYTES;
-        const uint8_t* sb = sa + BO * D_KT;
-#pragma unroll
-        for (int u = 0; u < D_KT / 32; ++u) {
-            v4i a[4], b[2];
-#pragma unroll
-            for (int f = 0; f < 4; ++f) a[f] = *tile_chunk<D_KT>(sa, wo * 128 + panel_row(f, row), 2 * u + q);
-#pragma unroll
-            for (int bb = 0; bb < 2; ++bb) b[bb] = *tile_chunk<D_KT>(sb, wt * 64 + bb * 32 + row, 2 * u + q);
-#pragma unroll
-            for (int f = 0; f < 4; ++f)
-#pragma unroll
-                for (int bb = 0; bb < 2; ++bb) acc[f][bb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(a[f], b[bb], acc[f][bb], 0, 0, 0);
+        if (round > 0) wg_barrier();                  // epilogue staging of the previous tile has been read out
+        issue(0);
+        if (nunits > 1) issue(1);
+        if (nunits > 1) wait_vmcnt<2 * ROW_LOADS>(); else wait_vmcnt<0>();
+        wg_barrier();                                 // unit 0 is published
+        int xi = 0;
+        read_frags(R0, 0);
+        wait_lgkm0();
+        if (grp == 1) { memory_phase(xi++); wg_barrier(); }   // the second wavefront of every SIMD runs one phase behind
+        for (int t = 0; t < S; t += 2) {
+            matrix_phase(R0, R1, t);     wg_barrier(); memory_phase(xi++); wg_barrier();
+            matrix_phase(R1, R0, t + 1); wg_barrier(); memory_phase(xi++); wg_barrier();
         }
+        if (grp == 0) wg_barrier();                   // realign the two groups; every wave is done with the operand tiles
+        if constexpr (!(DBG & 4)) store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
+        else keep_alive(acc, Y);
     }
-    store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * 64);
 }
 
-// ---- sparse INT8 over the lifted width: Y = X' . W'^T, W' packed 2:4 ----------------------------
-constexpr int S_KT = 128, S_STAGES = 3;
-constexpr int S_B_BYTES = BT * S_KT, S_AV_BYTES = BO * S_KT / 2, S_AM_BYTES = BO * S_KT / 8;
-constexpr int S_STAGE_BYTES = S_B_BYTES + S_AV_BYTES + S_AM_BYTES;
+// ---- sparse INT8 over the lifted width: Y = X' . W'^T, W' packed 2:4 ---------------------------------
+// Sub-step = 64 lifted columns.  Token tiles (B) move in units of two sub-steps (128-byte rows), ring
+// of 3; packed weights (A) in units of one sub-step (8 KB values + 2 KB index words), ring of 6.
+constexpr int S_B_UNIT = BT * ROWB;                 // 32 KB
+constexpr int S_AV_UNIT = BO * 32;                  // 8 KB
+constexpr int S_AM_UNIT = BO * 8;                   // 2 KB
+constexpr int S_NB = 3, S_NA = 6;
+constexpr int S_AV_OFF = S_NB * S_B_UNIT;
+constexpr int S_AM_OFF = S_AV_OFF + S_NA * S_AV_UNIT;
+constexpr int S_LDS = S_AM_OFF + S_NA * S_AM_UNIT;  // 159744 bytes
+static_assert(S_LDS <= 160 * 1024 && EP_TILE_BYTES <= S_LDS && EP_TILE_BYTES <= D_LDS, "LDS budget");
+constexpr int S_LB = ROW_LOADS, S_LA = 1;           // direct loads per thread: B unit, A unit values (+1 index load in waves 0, 1)
 
+struct SparseFrags { v4i a[4]; v4i idx; v8i b[NBF]; };
+
+template <int DBG>
 __global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restrict__ XL, const float* __restrict__ s_x, const uint8_t* __restrict__ w_vals,
                                                          const uint8_t* __restrict__ w_meta, const float* __restrict__ s_w, int64_t M, int64_t O,
                                                          int64_t Kp, uint16_t* __restrict__ Y, int64_t ldy, int tiles_o, int tiles_t)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
-    int to, tt;
-    tile_of_block(tiles_o, tiles_t, to, tt);
-    const int64_t o_blk = (int64_t)to * BO, t_blk = (int64_t)tt * BT;
-    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
-    const int wo = wave & 1, wt = wave >> 1;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR
+    const int wo = wave & 1, wt = wave >> 1, grp = wave >> 2;
     const int n = lane & 31, qb = lane >> 5;
-    const int nk = (int)(Kp / S_KT);
-    const int64_t nsteps = Kp / FRAG_K8;
+    const int S = (int)(Kp / FRAG_K8);               // sub-steps; even because K' % 128 == 0
     const int64_t npanels = (O + PANEL - 1) / PANEL;
-    constexpr int LPS = 4 + 2 + 1;    // B: 4, A values: 2, A index words: 1 (issued by waves 0..3 only; they wait on one more)
+    const bool meta_wave = wave < 2;                  // these two also fetch the index words (one panel each)
+    int brow[NBF];
+#pragma unroll
+    for (int bb = 0; bb < NBF; ++bb) brow[bb] = wt * (32 * NBF) + bb * 32 + n;
 
-    v16i acc[4][2];
-#pragma unroll
-    for (int f = 0; f < 4; ++f)
-#pragma unroll
-        for (int b = 0; b < 2; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[f][b][r] = 0;
-
-    auto issue = [&](int kt) {
-        uint8_t* st = smem + (kt % S_STAGES) * S_STAGE_BYTES;
-        load_rows_tile<S_KT>(XL, Kp, t_blk, M, (int64_t)kt * S_KT, st);
-        // A values: per panel the two 64-column steps of this stage are 8 KB contiguous
-#pragma unroll
-        for (int pp = 0; pp < 2; ++pp) {
-            int64_t panel = (int64_t)to * 2 + pp;
-            panel = panel < npanels ? panel : npanels - 1;
-            const uint8_t* src = w_vals + frag_slot(panel, nsteps, (int64_t)kt * 2, 0, 0) * 16;
-            lds_dma16(src + threadIdx.x * 16, st + S_B_BYTES + pp * 8192 + wave * 1024);
-        }
-        // A index words: 2 KB contiguous per panel
-        {
-            const int w4 = wave & 3;
-            int64_t panel = (int64_t)to * 2 + (w4 >> 1);
-            panel = panel < npanels ? panel : npanels - 1;
-            const uint8_t* src = w_meta + frag_slot(panel, nsteps, (int64_t)kt * 2, 0, 0) * 4 + (w4 & 1) * 1024;
-            // waves 4..7 repeat the loads of waves 0..3 (same bytes, same LDS address) so that
-            // every wave has the same number of loads in flight
-            lds_dma16(src + lane * 16, st + S_B_BYTES + S_AV_BYTES + w4 * 1024);
-        }
-    };
-#pragma unroll
-    for (int s = 0; s < S_STAGES - 1; ++s) if (s < nk) issue(s);
-
-    for (int kt = 0; kt < nk; ++kt) {
-        if (kt + S_STAGES - 2 < nk) wait_vmcnt<(S_STAGES - 2) * LPS>(); else wait_vmcnt<0>();
-        stage_barrier();
-        if (kt + S_STAGES - 1 < nk) issue(kt + S_STAGES - 1);
-        const uint8_t* sb = smem + (kt % S_STAGES) * S_STAGE_BYTES;
-        const uint8_t* sav = sb + S_B_BYTES;
-        const uint8_t* sam = sav + S_AV_BYTES;
-#pragma unroll
-        for (int u = 0; u < S_KT / 64; ++u) {
-            v4i a[4]; int idx[4]; v8i b[2];
-#pragma unroll
-            for (int f = 0; f < 4; ++f) {
-                const int fs = ((wo * 2 + u) * 4 + f) * 64 + lane;
-                a[f] = *reinterpret_cast<const v4i*>(sav + fs * 16);
-                idx[f] = *reinterpret_cast<const int*>(sam + fs * 4);
+    int to, tt;
+    for (int round = 0; tile_of_round(round, tiles_o, tiles_t, to, tt); ++round) {
+        const int64_t o_blk = (int64_t)to * BO, t_blk = (int64_t)tt * BT;
+        RowTileLoader lb;
+        lb.init(XL, Kp, t_blk, M, wave, lane);
+        // packed weights: one sub-step of a 128-channel panel is 4 KB of values and 1 KB of index words,
+        // both contiguous.  Values: waves 0..3 fetch panel 2*to, waves 4..7 panel 2*to+1, 16 bytes a lane.
+        int64_t vpanel = (int64_t)to * 2 + (wave >> 2), mpanel = (int64_t)to * 2 + (wave & 1);
+        vpanel = vpanel < npanels ? vpanel : npanels - 1;
+        mpanel = mpanel < npanels ? mpanel : npanels - 1;
+        const uint8_t* av_base = w_vals + (vpanel * S * 256 + (wave & 3) * 64) * 16;    // wave-uniform
+        const uint8_t* am_base = w_meta + mpanel * S * 1024;
+        const uint32_t lane16 = lane * 16;
+        auto issue_a = [&](int s) {
+            if constexpr (!(DBG & 1)) {
+                lds_dma16(av_base + (int64_t)s * 4096 + lane16, smem + S_AV_OFF + (s % S_NA) * S_AV_UNIT + wave * 1024);
+                if (meta_wave) lds_dma16(am_base + (int64_t)s * 1024 + lane16, smem + S_AM_OFF + (s % S_NA) * S_AM_UNIT + wave * 1024);
             }
+        };
+        auto issue_b = [&](int unit) {
+            if constexpr (!(DBG & 1)) lb.issue((int64_t)unit * ROWB, smem + (unit % S_NB) * S_B_UNIT, wave);
+        };
+
+        v16i acc[4][NBF];
+        zero_acc(acc);
+        SparseFrags R0, R1;
+        auto read_frags = [&](SparseFrags& R, int t) {
+            if constexpr (!(DBG & 2)) {
+                const uint8_t* sav = smem + S_AV_OFF + (t % S_NA) * S_AV_UNIT;
+                const uint8_t* sam = smem + S_AM_OFF + (t % S_NA) * S_AM_UNIT;
+                const uint8_t* sb = smem + ((t >> 1) % S_NB) * S_B_UNIT;
 #pragma unroll
-            for (int bb = 0; bb < 2; ++bb) {
-                const int r = wt * 64 + bb * 32 + n;
-                const v4i lo = *tile_chunk<S_KT>(sb, r, 4 * u + 2 * qb);
-                const v4i hi = *tile_chunk<S_KT>(sb, r, 4 * u + 2 * qb + 1);
-                b[bb] = (v8i){lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                for (int f = 0; f < 4; ++f) R.a[f] = *reinterpret_cast<const v4i*>(sav + ((wo * 4 + f) * 64 + lane) * 16);
+                R.idx = *reinterpret_cast<const v4i*>(sam + (wo * 64 + lane) * 16);
+                const int lc = 4 * (t & 1) + 2 * qb;
+#pragma unroll
+                for (int bb = 0; bb < NBF; ++bb) {
+                    const v4i lo = *tile_chunk(sb, brow[bb], lc);
+                    const v4i hi = *tile_chunk(sb, brow[bb], lc + 1);
+                    R.b[bb] = (v8i){lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                }
             }
+        };
+        // matrix phase of sub-step t: first put the operand reads of sub-step t+1 in flight, then issue the
+        // eight matrix instructions of sub-step t
+        auto matrix_phase = [&](const SparseFrags& cur, SparseFrags& nxt, int t) {
+            if (t + 1 < S) read_frags(nxt, t + 1);
+            if constexpr (!(DBG & 2)) {
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int f = 0; f < 4; ++f)
+                for (int f = 0; f < 4; ++f)
 #pragma unroll
-                for (int bb = 0; bb < 2; ++bb) acc[f][bb] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(a[f], b[bb], acc[f][bb], idx[f], 0, 0);
+                    for (int bb = 0; bb < NBF; ++bb)
+                        acc[f][bb] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(cur.a[f], cur.b[bb], acc[f][bb], cur.idx[f], 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            wait_lgkm0();                                 // the reads of t+1 have returned before the next barrier
+        };
+        // Memory phase number xi of this wavefront (its partner on the SIMD is in a matrix phase): wait
+        // until this wave's loads of sub-step xi+2 have landed (two barriers later the first wavefront reads
+        // them), then request A sub-step xi+6 and, at odd xi, B unit (xi+1)/2+2 into ring slots whose last
+        // readers finished before the previous barrier.  In flight behind the awaited loads are the
+        // requests of the three previous memory phases: three A requests and one B request.
+        auto memory_phase = [&](int xi, bool steady) {
+            if (xi + 2 < S) {
+                if (steady) { if (meta_wave) wait_vmcnt<3 * (S_LA + 1) + S_LB>(); else wait_vmcnt<3 * S_LA + S_LB>(); }
+                else wait_vmcnt<0>();
+            }
+            if ((xi & 1) && ((xi + 1) >> 1) + 2 < (S >> 1)) issue_b(((xi + 1) >> 1) + 2);
+            if (xi + 6 < S) issue_a(xi + 6);
+        };
+
+        // Prologue: sub-steps 0 and 1 first, then A2 | B1 A3 | A4 | B2 A5, the order later phases keep.
+        if (round > 0) wg_barrier();                  // epilogue staging of the previous tile has been read out
+        issue_b(0); issue_a(0); if (1 < S) issue_a(1);
+        if (2 < S) issue_a(2);
+        if (2 < S) issue_b(1); if (3 < S) issue_a(3);
+        if (4 < S) issue_a(4);
+        if (4 < S) issue_b(2); if (5 < S) issue_a(5);
+        const bool long_k = S >= 14;                  // short k: plain full waits everywhere
+        if (!long_k) wait_vmcnt<0>();
+        else if (meta_wave) wait_vmcnt<4 * (S_LA + 1) + 2 * S_LB>();
+        else wait_vmcnt<4 * S_LA + 2 * S_LB>();
+        wg_barrier();                                 // sub-steps 0 and 1 are published
+        int xi = 0;
+        read_frags(R0, 0);
+        wait_lgkm0();
+        wg_barrier();                                 // everyone holds the operands of sub-step 0: its ring slot may be refilled
+        if (grp == 1) { memory_phase(xi, long_k); ++xi; wg_barrier(); }   // the second wavefront of every SIMD runs one phase behind
+        int t = 0;
+        if (long_k) {
+            for (; xi + 8 < S; t += 2) {              // every memory phase of the trip is a full one
+                matrix_phase(R0, R1, t);     wg_barrier(); memory_phase(xi++, true); wg_barrier();
+                matrix_phase(R1, R0, t + 1); wg_barrier(); memory_phase(xi++, true); wg_barrier();
+            }
         }
+        for (; t < S; t += 2) {
+            matrix_phase(R0, R1, t);     wg_barrier(); memory_phase(xi++, false); wg_barrier();
+            matrix_phase(R1, R0, t + 1); wg_barrier(); memory_phase(xi++, false); wg_barrier();
+        }
+        if (grp == 0) wg_barrier();                   // realign the two groups; every wave is done with the operand tiles
+        if constexpr (!(DBG & 4)) store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
+        else keep_alive(acc, Y);
     }
-    store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * 64);
 }
 
 }  // namespace ss
 
 using namespace ss;
+
+// one persistent workgroup per compute unit of the current device (fewer if there are fewer tiles)
+static int persistent_grid(int ntiles)
+{
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return -1;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return -1;
+    return ntiles < cus ? ntiles : cus;
+}
 
 static ss_status check_gemm(const void* X, const float* s_x, const void* W, const float* s_w, int64_t M, int64_t O, int64_t K,
                             ss_dtype dtype, const void* Y, int64_t ldy)
@@ -292,15 +490,19 @@ extern "C" ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq
 {
     ss_status st = check_gemm(Xq, s_x, Wq, s_w, M, O, K, dtype, Y, ldy);
     if (st != SS_OK || M == 0 || O == 0) return st;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)k_dense_i8, hipFuncAttributeMaxDynamicSharedMemorySize, D_STAGES * D_STAGE_BYTES) != hipSuccess) return SS_ERR_HIP;
-        attr_set = true;
-    }
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
-    hipLaunchKernelGGL(k_dense_i8, dim3(tiles_o * tiles_t), dim3(G_THREADS), D_STAGES * D_STAGE_BYTES, static_cast<hipStream_t>(stream),
-                       static_cast<const uint8_t*>(Xq), s_x, static_cast<const uint8_t*>(Wq), s_w, M, O, K, static_cast<uint16_t*>(Y), ldy,
-                       tiles_o, tiles_t);
+    const int grid = persistent_grid(tiles_o * tiles_t);
+    if (grid <= 0) return SS_ERR_HIP;
+    const int dbg = getenv("SS_DBG") ? atoi(getenv("SS_DBG")) : 0;
+#define SS_LAUNCH_DENSE(D)                                                                                                              \
+    do {                                                                                                                                \
+        if (hipFuncSetAttribute((const void*)k_dense_i8<D>, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS) != hipSuccess) return SS_ERR_HIP; \
+        hipLaunchKernelGGL((k_dense_i8<D>), dim3(grid), dim3(G_THREADS), D_LDS, static_cast<hipStream_t>(stream),               \
+                           static_cast<const uint8_t*>(Xq), s_x, static_cast<const uint8_t*>(Wq), s_w, M, O, K, static_cast<uint16_t*>(Y), \
+                           ldy, tiles_o, tiles_t);                                                                                       \
+    } while (0)
+    if (dbg == 5) SS_LAUNCH_DENSE(5); else if (dbg == 6) SS_LAUNCH_DENSE(6); else if (dbg == 4) SS_LAUNCH_DENSE(4); else SS_LAUNCH_DENSE(0);
+#undef SS_LAUNCH_DENSE
     return launch_status();
 }
 
@@ -311,15 +513,19 @@ extern "C" ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, c
     if (st != SS_OK || M == 0 || O == 0) return st;
     if (!w_meta) return SS_ERR_NULL;
     if ((uintptr_t)w_meta & 15) return SS_ERR_SHAPE;
-    static bool attr_set = false;
-    if (!attr_set) {
-        if (hipFuncSetAttribute((const void*)k_sparse_i8, hipFuncAttributeMaxDynamicSharedMemorySize, S_STAGES * S_STAGE_BYTES) != hipSuccess) return SS_ERR_HIP;
-        attr_set = true;
-    }
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
-    hipLaunchKernelGGL(k_sparse_i8, dim3(tiles_o * tiles_t), dim3(G_THREADS), S_STAGES * S_STAGE_BYTES, static_cast<hipStream_t>(stream),
-                       static_cast<const uint8_t*>(X_lifted), s_x, static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w,
-                       M, O, K_lifted, static_cast<uint16_t*>(Y), ldy, tiles_o, tiles_t);
+    const int grid = persistent_grid(tiles_o * tiles_t);
+    if (grid <= 0) return SS_ERR_HIP;
+    const int dbg = getenv("SS_DBG") ? atoi(getenv("SS_DBG")) : 0;
+#define SS_LAUNCH_SPARSE(D)                                                                                                             \
+    do {                                                                                                                                \
+        if (hipFuncSetAttribute((const void*)k_sparse_i8<D>, hipFuncAttributeMaxDynamicSharedMemorySize, S_LDS) != hipSuccess) return SS_ERR_HIP; \
+        hipLaunchKernelGGL((k_sparse_i8<D>), dim3(grid), dim3(G_THREADS), S_LDS, static_cast<hipStream_t>(stream),              \
+                           static_cast<const uint8_t*>(X_lifted), s_x, static_cast<const uint8_t*>(w_vals),                               \
+                           static_cast<const uint8_t*>(w_meta), s_w, M, O, K_lifted, static_cast<uint16_t*>(Y), ldy, tiles_o, tiles_t);    \
+    } while (0)
+    if (dbg == 21) SS_LAUNCH_SPARSE(21); else if (dbg == 37) SS_LAUNCH_SPARSE(37); else if (dbg == 36) SS_LAUNCH_SPARSE(36); else if (dbg == 5) SS_LAUNCH_SPARSE(5); else if (dbg == 6) SS_LAUNCH_SPARSE(6); else if (dbg == 4) SS_LAUNCH_SPARSE(4); else SS_LAUNCH_SPARSE(0);
+#undef SS_LAUNCH_SPARSE
     return launch_status();
 }
 

@@ -31,7 +31,8 @@ __host__ __device__ inline int panel_row(int f, int i) { return 64 * ((i >> 2) &
 // window (0..15) inside a 64-column step held by lane half qa at window slot w (0..7)
 __host__ __device__ inline int step_window(int qa, int w) { return 8 * (w >> 2) + 4 * qa + (w & 3); }
 
-// byte offset of the 16-byte value group / 4-byte index word of (panel, step, fragment, lane)
+// slot of the 16-byte value group of (panel, step, fragment, lane); values are stored [panel][step][fragment][lane],
+// index words [panel][step][lane][fragment] so that one 16-byte read hands a lane the words of all four fragments
 __host__ __device__ inline int64_t frag_slot(int64_t panel, int64_t nsteps, int64_t step, int f, int lane)
 {
     return ((panel * nsteps + step) * FRAGS_PER_PANEL + f) * 64 + lane;

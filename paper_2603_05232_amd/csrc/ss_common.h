@@ -4,7 +4,7 @@
 #include <stdint.h>
 #include "slidesparse.h"
 
-#define SS_FORMAT_VERSION 1
+#define SS_FORMAT_VERSION 2
 
 namespace ss {
 
