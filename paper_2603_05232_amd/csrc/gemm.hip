@@ -271,35 +271,41 @@ __global__ __launch_bounds__(G_THREADS) void k_dense_i8(const uint8_t* __restric
         v16i acc[4][NBF];
         zero_acc(acc);
         DenseFrags R0, R1;
-        auto read_frags = [&](DenseFrags& R, int t) {
+        // one operand read of sub-step t: parts 0..3 are the weight fragments, 4..5 the token fragments
+        auto read_part = [&](DenseFrags& R, int t, int part) {
             if constexpr (!(DBG & 2)) {
                 const uint8_t* sa = smem + ((t >> 2) & 1) * D_UNIT;
-                const uint8_t* sb = sa + 2 * D_UNIT;
                 const int lc = 2 * (t & 3) + q;
-#pragma unroll
-                for (int f = 0; f < 4; ++f) R.a[f] = *tile_chunk(sa, arow[f], lc);
-#pragma unroll
-                for (int bb = 0; bb < NBF; ++bb) R.b[bb] = *tile_chunk(sb, brow[bb], lc);
+                if (part < 4) R.a[part] = *tile_chunk(sa, arow[part], lc);
+                else R.b[part - 4] = *tile_chunk(sa + 2 * D_UNIT, brow[part - 4], lc);
             }
         };
-        // matrix phase of sub-step t: first put the operand reads of sub-step t+1 in flight, then issue the
-        // eight matrix instructions of sub-step t
-        auto matrix_phase = [&](const DenseFrags& cur, DenseFrags& nxt, int t) {
-            if (t + 1 < S) read_frags(nxt, t + 1);
+        auto read_frags = [&](DenseFrags& R, int t) {
+#pragma unroll
+            for (int part = 0; part < 4 + NBF; ++part) read_part(R, t, part);
+        };
+        // Matrix phase of sub-step t: the eight matrix instructions of sub-step t with the operand reads of
+        // sub-step t+1 placed one by one behind them.  A wavefront issues in order and a read waits for room
+        // in the LDS queue, which the three other SIMDs fill at the same time: reads bunched in front of the
+        // matrix instructions keep the matrix pipe idle for as long as the LDS takes to serve them.
+        auto matrix_phase = [&](const DenseFrags& cur, DenseFrags& nxt, int t, auto prefetch) {
             if constexpr (!(DBG & 2)) {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int f = 0; f < 4; ++f)
-#pragma unroll
-                    for (int bb = 0; bb < NBF; ++bb) acc[f][bb] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[f], cur.b[bb], acc[f][bb], 0, 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int i = 0; i < 4 * NBF; ++i) {
+                    acc[i / NBF][i % NBF] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i / NBF], cur.b[i % NBF], acc[i / NBF][i % NBF], 0, 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (decltype(prefetch)::value) {
+                        if (i < 4 + NBF) { read_part(nxt, t + 1, i); __builtin_amdgcn_sched_barrier(0); }
+                    }
+                }
             }
-            wait_lgkm0();                                 // the reads of t+1 have returned before the next barrier
         };
         // memory phase number xi of this wavefront (its partner on the SIMD is in a matrix phase).  Unit
         // j = sub-steps 4j..4j+3: it is awaited at xi = 4j - 2 and, once its ring slot is free, the unit two
         // ahead is requested at xi = 4j + 3.
         auto memory_phase = [&](int xi) {
+            wait_lgkm0();                             // operand reads of the matrix phase just finished have returned
             if ((xi & 3) == 2 && ((xi + 2) >> 2) < nunits) wait_vmcnt<0>();
             if ((xi & 3) == 3 && ((xi + 1) >> 2) + 1 < nunits) issue(((xi + 1) >> 2) + 1);
         };
@@ -313,10 +319,13 @@ __global__ __launch_bounds__(G_THREADS) void k_dense_i8(const uint8_t* __restric
         read_frags(R0, 0);
         wait_lgkm0();
         if (grp == 1) { memory_phase(xi++); wg_barrier(); }   // the second wavefront of every SIMD runs one phase behind
-        for (int t = 0; t < S; t += 2) {
-            matrix_phase(R0, R1, t);     wg_barrier(); memory_phase(xi++); wg_barrier();
-            matrix_phase(R1, R0, t + 1); wg_barrier(); memory_phase(xi++); wg_barrier();
+        int t = 0;
+        for (; t + 2 < S; t += 2) {
+            matrix_phase(R0, R1, t, std::true_type{});     wg_barrier(); memory_phase(xi++); wg_barrier();
+            matrix_phase(R1, R0, t + 1, std::true_type{}); wg_barrier(); memory_phase(xi++); wg_barrier();
         }
+        matrix_phase(R0, R1, t, std::true_type{});      wg_barrier(); memory_phase(xi++); wg_barrier();
+        matrix_phase(R1, R0, t + 1, std::false_type{}); wg_barrier(); memory_phase(xi++); wg_barrier();
         if (grp == 0) wg_barrier();                   // realign the two groups; every wave is done with the operand tiles
         if constexpr (!(DBG & 4)) store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
         else keep_alive(acc, Y);
@@ -380,37 +389,42 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restri
         v16i acc[4][NBF];
         zero_acc(acc);
         SparseFrags R0, R1;
-        auto read_frags = [&](SparseFrags& R, int t) {
+        // one operand read of sub-step t: parts 0..3 weight values, 4 their index words, 5..8 the two
+        // halves of the two token fragments
+        auto read_part = [&](SparseFrags& R, int t, int part) {
             if constexpr (!(DBG & 2)) {
-                const uint8_t* sav = smem + S_AV_OFF + (t % S_NA) * S_AV_UNIT;
-                const uint8_t* sam = smem + S_AM_OFF + (t % S_NA) * S_AM_UNIT;
-                const uint8_t* sb = smem + ((t >> 1) % S_NB) * S_B_UNIT;
+                if (part < 4) R.a[part] = *reinterpret_cast<const v4i*>(smem + S_AV_OFF + (t % S_NA) * S_AV_UNIT + ((wo * 4 + part) * 64 + lane) * 16);
+                else if (part == 4) R.idx = *reinterpret_cast<const v4i*>(smem + S_AM_OFF + (t % S_NA) * S_AM_UNIT + (wo * 64 + lane) * 16);
+                else {
+                    const int bb = (part - 5) >> 1, h = (part - 5) & 1;
+                    const v4i v = *tile_chunk(smem + ((t >> 1) % S_NB) * S_B_UNIT, brow[bb], 4 * (t & 1) + 2 * qb + h);
 #pragma unroll
-                for (int f = 0; f < 4; ++f) R.a[f] = *reinterpret_cast<const v4i*>(sav + ((wo * 4 + f) * 64 + lane) * 16);
-                R.idx = *reinterpret_cast<const v4i*>(sam + (wo * 64 + lane) * 16);
-                const int lc = 4 * (t & 1) + 2 * qb;
-#pragma unroll
-                for (int bb = 0; bb < NBF; ++bb) {
-                    const v4i lo = *tile_chunk(sb, brow[bb], lc);
-                    const v4i hi = *tile_chunk(sb, brow[bb], lc + 1);
-                    R.b[bb] = (v8i){lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                    for (int e = 0; e < 4; ++e) R.b[bb][4 * h + e] = v[e];
                 }
             }
         };
-        // matrix phase of sub-step t: first put the operand reads of sub-step t+1 in flight, then issue the
-        // eight matrix instructions of sub-step t
-        auto matrix_phase = [&](const SparseFrags& cur, SparseFrags& nxt, int t) {
-            if (t + 1 < S) read_frags(nxt, t + 1);
+        auto read_frags = [&](SparseFrags& R, int t) {
+#pragma unroll
+            for (int part = 0; part < 9; ++part) read_part(R, t, part);
+        };
+        // Matrix phase of sub-step t: the eight matrix instructions of sub-step t with the operand reads of
+        // sub-step t+1 placed one by one behind them.  A wavefront issues in order and a read waits for room
+        // in the LDS queue, which the three other SIMDs fill at the same time: reads bunched in front of the
+        // matrix instructions keep the matrix pipe idle for as long as the LDS takes to serve them.
+        auto matrix_phase = [&](const SparseFrags& cur, SparseFrags& nxt, int t, auto prefetch) {
             if constexpr (!(DBG & 2)) {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int f = 0; f < 4; ++f)
-#pragma unroll
-                    for (int bb = 0; bb < NBF; ++bb)
-                        acc[f][bb] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(cur.a[f], cur.b[bb], acc[f][bb], cur.idx[f], 0, 0);
-                __builtin_amdgcn_sched_barrier(0);
+                for (int i = 0; i < 4 * NBF; ++i) {
+                    acc[i / NBF][i % NBF] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(cur.a[i / NBF], cur.b[i % NBF], acc[i / NBF][i % NBF], cur.idx[i / NBF], 0, 0);
+                    __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (decltype(prefetch)::value) {
+                        read_part(nxt, t + 1, i);
+                        if (i == 7) read_part(nxt, t + 1, 8);
+                        __builtin_amdgcn_sched_barrier(0);
+                    }
+                }
             }
-            wait_lgkm0();                                 // the reads of t+1 have returned before the next barrier
         };
         // Memory phase number xi of this wavefront (its partner on the SIMD is in a matrix phase): wait
         // until this wave's loads of sub-step xi+2 have landed (two barriers later the first wavefront reads
@@ -418,10 +432,12 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restri
         // readers finished before the previous barrier.  In flight behind the awaited loads are the
         // requests of the three previous memory phases: three A requests and one B request.
         auto memory_phase = [&](int xi, bool steady) {
+            // (the waits below also cover this wave's operand reads of the matrix phase just finished, which
+            // must have returned before their ring slots are refilled after the next barrier)
             if (xi + 2 < S) {
                 if (steady) { if (meta_wave) wait_vmcnt<3 * (S_LA + 1) + S_LB>(); else wait_vmcnt<3 * S_LA + S_LB>(); }
                 else wait_vmcnt<0>();
-            }
+            } else wait_lgkm0();
             if ((xi & 1) && ((xi + 1) >> 1) + 2 < (S >> 1)) issue_b(((xi + 1) >> 1) + 2);
             if (xi + 6 < S) issue_a(xi + 6);
         };
@@ -446,14 +462,28 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restri
         int t = 0;
         if (long_k) {
             for (; xi + 8 < S; t += 2) {              // every memory phase of the trip is a full one
-                matrix_phase(R0, R1, t);     wg_barrier(); memory_phase(xi++, true); wg_barrier();
-                matrix_phase(R1, R0, t + 1); wg_barrier(); memory_phase(xi++, true); wg_barrier();
+                if constexpr (DBG & 32) {
+                    long long c0 = __builtin_readcyclecounter();
+                    matrix_phase(R0, R1, t, std::true_type{}); long long c1 = __builtin_readcyclecounter();
+                    wg_barrier(); long long c2 = __builtin_readcyclecounter();
+                    memory_phase(xi++, true); long long c3 = __builtin_readcyclecounter();
+                    wg_barrier(); long long c4 = __builtin_readcyclecounter();
+                    if (blockIdx.x == 0 && round == 0 && lane == 0 && t >= 20 && t < 36) {
+                        long long* o = reinterpret_cast<long long*>(Y) + (wave * 8 + (t - 20) / 2) * 4;
+                        o[0] = c1 - c0; o[1] = c2 - c1; o[2] = c3 - c2; o[3] = c4 - c3;
+                    }
+                } else {
+                matrix_phase(R0, R1, t, std::true_type{});     wg_barrier(); memory_phase(xi++, true); wg_barrier();
+                }
+                matrix_phase(R1, R0, t + 1, std::true_type{}); wg_barrier(); memory_phase(xi++, true); wg_barrier();
             }
         }
-        for (; t < S; t += 2) {
-            matrix_phase(R0, R1, t);     wg_barrier(); memory_phase(xi++, false); wg_barrier();
-            matrix_phase(R1, R0, t + 1); wg_barrier(); memory_phase(xi++, false); wg_barrier();
+        for (; t + 2 < S; t += 2) {
+            matrix_phase(R0, R1, t, std::true_type{});     wg_barrier(); memory_phase(xi++, false); wg_barrier();
+            matrix_phase(R1, R0, t + 1, std::true_type{}); wg_barrier(); memory_phase(xi++, false); wg_barrier();
         }
+        matrix_phase(R0, R1, t, std::true_type{});      wg_barrier(); memory_phase(xi++, false); wg_barrier();
+        matrix_phase(R1, R0, t + 1, std::false_type{}); wg_barrier(); memory_phase(xi++, false); wg_barrier();
         if (grp == 0) wg_barrier();                   // realign the two groups; every wave is done with the operand tiles
         if constexpr (!(DBG & 4)) store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
         else keep_alive(acc, Y);
