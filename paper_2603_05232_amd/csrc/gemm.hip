@@ -12,18 +12,20 @@
 // lane-contiguous LDS) so the 32 lanes of an operand read hit all 64 banks.
 //
 // Schedule.  The k loop advances in sub-steps of one matrix-instruction depth (64 lifted columns
-// sparse, 32 columns dense).  Every wavefront alternates a read phase (wait for its landed loads,
-// request new units, fetch the operand registers of its next sub-step from LDS) and a matrix phase
-// (eight back-to-back matrix instructions), separated by workgroup barriers.  The two wavefronts that
-// share a SIMD run half a sub-step apart, so while one issues matrix instructions the other does its
-// memory work and the matrix pipe always has a feeder.
+// sparse, 32 columns dense): eight matrix instructions per wavefront, with the LDS reads of the next
+// sub-step's operands (double-buffered registers) and a share of the direct loads of a later unit
+// placed one by one between them -- a wavefront issues in order, and an LDS read or a load that has to
+// wait for room in its queue keeps the matrix instructions behind it from issuing, so neither kind is
+// issued in bursts.  The two wavefronts of a SIMD run freely against each other and fill each other's
+// gaps; the workgroup meets at one barrier per unit (128 k-bytes), where the landed next unit is
+// published and the ring slot of the finished unit is handed back to the loaders.
 //
 // Epilogue.  D[channel][token] leaves each lane with 64 consecutive output channels of one token; the
 // scaled bf16 values are staged through the (then idle) LDS so that every global store instruction
 // writes whole 256-byte row segments.
 #include "ss_common.h"
 #include "packed_layout.h"
-#include <cstdlib>
+#include <type_traits>
 
 
 namespace ss {
@@ -86,10 +88,7 @@ __device__ inline bool tile_of_round(int round, int tiles_o, int tiles_t, int& t
     if (base + bid >= total) return false;
     int tile = base + bid;
     if (base + nb <= total && (nb & 7) == 0) tile = base + (bid & 7) * (nb >> 3) + (bid >> 3);
-#ifndef SS_BAND
-#define SS_BAND 8
-#endif
-    constexpr int BAND = SS_BAND;
+    constexpr int BAND = 8;
     const int per_band = BAND * tiles_o;
     const int band = tile / per_band, within = tile - band * per_band;
     const int bw = min(BAND, tiles_t - band * BAND);
@@ -119,11 +118,14 @@ struct RowTileLoader {
             off[i] = (uint32_t)((grow - row0) * ld) + lc * 16;
         }
     }
+    __device__ void issue_one(int i, int64_t k0, uint8_t* lds_tile, int wave) const
+    {
+        lds_dma16(base + k0 + off[i], lds_tile + (i * G_WAVES + wave) * 8 * ROWB);
+    }
     __device__ void issue(int64_t k0, uint8_t* lds_tile, int wave) const
     {
-        const uint8_t* b = base + k0;
 #pragma unroll
-        for (int i = 0; i < ROW_LOADS; ++i) lds_dma16(b + off[i], lds_tile + (i * G_WAVES + wave) * 8 * ROWB);
+        for (int i = 0; i < ROW_LOADS; ++i) issue_one(i, k0, lds_tile, wave);
     }
 };
 
@@ -216,22 +218,6 @@ template <typename ACC> __device__ inline void zero_acc(ACC (&acc)[4][NBF])
             for (int r = 0; r < 16; ++r) acc[f][b][r] = 0;
 }
 
-// debug variants that skip the epilogue still have to consume the accumulators
-template <typename ACC> __device__ inline void keep_alive(const ACC (&acc)[4][NBF], uint16_t* Y)
-{
-    int sum = 0;
-#pragma unroll
-    for (int f = 0; f < 4; ++f)
-#pragma unroll
-        for (int b = 0; b < NBF; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) sum += (int)acc[f][b][r];
-    if (sum == 0x7fffffff) Y[0] = 1;
-}
-
-// Phase groups: wavefronts w and w + 4 of a workgroup share a SIMD (checked on the device), so the two
-// groups that run half a sub-step apart are waves {0..3} and {4..7}: grp = wave >> 2.
-
 // ---- dense INT8: Y = Xq . Wq^T -------------------------------------------------------------------
 // Units of 128 k-bytes (4 sub-steps of the 32x32x32 instruction); rings of two units per operand.
 constexpr int D_UNIT = BO * ROWB;                   // 32 KB, same for A and B
@@ -239,17 +225,15 @@ constexpr int D_LDS = EP_TILE_BYTES > 4 * D_UNIT ? EP_TILE_BYTES : 4 * D_UNIT;  
 
 struct DenseFrags { v4i a[4]; v4i b[NBF]; };
 
-template <int DBG>
 __global__ __launch_bounds__(G_THREADS) void k_dense_i8(const uint8_t* __restrict__ Xq, const float* __restrict__ s_x, const uint8_t* __restrict__ Wq,
                                                         const float* __restrict__ s_w, int64_t M, int64_t O, int64_t K, uint16_t* __restrict__ Y,
                                                         int64_t ldy, int tiles_o, int tiles_t)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR
-    const int wo = wave & 1, wt = wave >> 1, grp = wave >> 2;
+    const int wo = wave & 1, wt = wave >> 1;
     const int row = lane & 31, q = lane >> 5;
     const int nunits = (int)(K / ROWB);
-    const int S = 4 * nunits;
     int arow[4], brow[NBF];
 #pragma unroll
     for (int f = 0; f < 4; ++f) arow[f] = wo * 128 + panel_row(f, row);
@@ -262,103 +246,122 @@ __global__ __launch_bounds__(G_THREADS) void k_dense_i8(const uint8_t* __restric
         RowTileLoader la, lb;
         la.init(Wq, K, o_blk, O, wave, lane);
         lb.init(Xq, K, t_blk, M, wave, lane);
-        auto issue = [&](int unit) {
-            if constexpr (!(DBG & 1)) {
-                la.issue((int64_t)unit * ROWB, smem + (unit & 1) * D_UNIT, wave);
-                lb.issue((int64_t)unit * ROWB, smem + 2 * D_UNIT + (unit & 1) * D_UNIT, wave);
+        // direct load number j (0..7) of this wavefront for a unit: weight and token rows alternate
+        auto issue_part = [&](int unit, int j) {
+            {
+                if (j & 1) lb.issue_one(j >> 1, (int64_t)unit * ROWB, smem + 2 * D_UNIT + (unit & 1) * D_UNIT, wave);
+                else la.issue_one(j >> 1, (int64_t)unit * ROWB, smem + (unit & 1) * D_UNIT, wave);
             }
+        };
+        auto issue = [&](int unit) {
+#pragma unroll
+            for (int j = 0; j < 2 * ROW_LOADS; ++j) issue_part(unit, j);
         };
         v16i acc[4][NBF];
         zero_acc(acc);
         DenseFrags R0, R1;
         // one operand read of sub-step t: parts 0..3 are the weight fragments, 4..5 the token fragments
         auto read_part = [&](DenseFrags& R, int t, int part) {
-            if constexpr (!(DBG & 2)) {
+            {
                 const uint8_t* sa = smem + ((t >> 2) & 1) * D_UNIT;
                 const int lc = 2 * (t & 3) + q;
                 if (part < 4) R.a[part] = *tile_chunk(sa, arow[part], lc);
                 else R.b[part - 4] = *tile_chunk(sa + 2 * D_UNIT, brow[part - 4], lc);
             }
         };
-        auto read_frags = [&](DenseFrags& R, int t) {
-#pragma unroll
-            for (int part = 0; part < 4 + NBF; ++part) read_part(R, t, part);
-        };
-        // Matrix phase of sub-step t: the eight matrix instructions of sub-step t with the operand reads of
-        // sub-step t+1 placed one by one behind them.  A wavefront issues in order and a read waits for room
-        // in the LDS queue, which the three other SIMDs fill at the same time: reads bunched in front of the
-        // matrix instructions keep the matrix pipe idle for as long as the LDS takes to serve them.
-        auto matrix_phase = [&](const DenseFrags& cur, DenseFrags& nxt, int t, auto prefetch) {
-            if constexpr (!(DBG & 2)) {
+        // Sub-step t: its eight matrix instructions, with the operand reads of sub-step t+1 placed one by
+        // one behind them.  A wavefront issues in order and an LDS read waits for room in the LDS queue,
+        // which the other SIMDs and the arriving direct loads fill too: reads bunched in front of the
+        // matrix instructions would idle the matrix pipe for as long as the LDS takes to accept them.
+        // loads = 1 / 2: the first / second four direct loads of unit `lunit` are issued on the way, one
+        // behind every second matrix instruction: a burst of loads from all wavefronts fills the queue of the
+        // memory pipeline, and a wavefront whose load issue waits for room there issues no matrix instructions.
+        auto sub_step = [&](const DenseFrags& cur, DenseFrags& nxt, int t, auto prefetch, auto loads, int lunit) {
+            {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < 4 * NBF; ++i) {
                     acc[i / NBF][i % NBF] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i / NBF], cur.b[i % NBF], acc[i / NBF][i % NBF], 0, 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (decltype(loads)::value > 0) {
+                        if (i & 1) { issue_part(lunit, 4 * (decltype(loads)::value - 1) + (i >> 1)); __builtin_amdgcn_sched_barrier(0); }
+                    }
                     if constexpr (decltype(prefetch)::value) {
                         if (i < 4 + NBF) { read_part(nxt, t + 1, i); __builtin_amdgcn_sched_barrier(0); }
                     }
                 }
             }
         };
-        // memory phase number xi of this wavefront (its partner on the SIMD is in a matrix phase).  Unit
-        // j = sub-steps 4j..4j+3: it is awaited at xi = 4j - 2 and, once its ring slot is free, the unit two
-        // ahead is requested at xi = 4j + 3.
-        auto memory_phase = [&](int xi) {
-            wait_lgkm0();                             // operand reads of the matrix phase just finished have returned
-            if ((xi & 3) == 2 && ((xi + 2) >> 2) < nunits) wait_vmcnt<0>();
-            if ((xi & 3) == 3 && ((xi + 1) >> 2) + 1 < nunits) issue(((xi + 1) >> 2) + 1);
-        };
 
+        // Unit u+2 is requested into the ring slot of unit u once every wavefront holds the operands of
+        // the last sub-step of unit u, and is awaited one unit later.
         if (round > 0) wg_barrier();                  // epilogue staging of the previous tile has been read out
         issue(0);
         if (nunits > 1) issue(1);
         if (nunits > 1) wait_vmcnt<2 * ROW_LOADS>(); else wait_vmcnt<0>();
         wg_barrier();                                 // unit 0 is published
-        int xi = 0;
-        read_frags(R0, 0);
+#pragma unroll
+        for (int part = 0; part < 4 + NBF; ++part) read_part(R0, 0, part);
         wait_lgkm0();
-        if (grp == 1) { memory_phase(xi++); wg_barrier(); }   // the second wavefront of every SIMD runs one phase behind
-        int t = 0;
-        for (; t + 2 < S; t += 2) {
-            matrix_phase(R0, R1, t, std::true_type{});     wg_barrier(); memory_phase(xi++); wg_barrier();
-            matrix_phase(R1, R0, t + 1, std::true_type{}); wg_barrier(); memory_phase(xi++); wg_barrier();
+        constexpr std::integral_constant<int, 0> no_loads{};
+        constexpr std::integral_constant<int, 1> first_half{};
+        constexpr std::integral_constant<int, 2> second_half{};
+        constexpr std::true_type prefetch{};
+        int t = 0, u = 0;
+        sub_step(R0, R1, t, prefetch, no_loads, 0);     wait_lgkm0();
+        sub_step(R1, R0, t + 1, prefetch, no_loads, 0); wait_lgkm0();
+        sub_step(R0, R1, t + 2, prefetch, no_loads, 0);
+        for (; u + 2 < nunits; ++u, t += 4) {         // unit u+1 is in flight, unit u+2 gets requested
+            wait_vmcnt<0>();                          // unit u+1 has landed (and the reads of t+3 have returned)
+            wg_barrier();                             // ... for every wavefront; nobody reads unit u's slot any more
+            sub_step(R1, R0, t + 3, prefetch, first_half, u + 2);  wait_lgkm0();
+            sub_step(R0, R1, t + 4, prefetch, second_half, u + 2); wait_lgkm0();
+            sub_step(R1, R0, t + 5, prefetch, no_loads, 0);        wait_lgkm0();
+            sub_step(R0, R1, t + 6, prefetch, no_loads, 0);
         }
-        matrix_phase(R0, R1, t, std::true_type{});      wg_barrier(); memory_phase(xi++); wg_barrier();
-        matrix_phase(R1, R0, t + 1, std::false_type{}); wg_barrier(); memory_phase(xi++); wg_barrier();
-        if (grp == 0) wg_barrier();                   // realign the two groups; every wave is done with the operand tiles
-        if constexpr (!(DBG & 4)) store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
-        else keep_alive(acc, Y);
+        if (u + 1 < nunits) {                         // the last unit follows without further requests
+            wait_vmcnt<0>();
+            wg_barrier();
+            sub_step(R1, R0, t + 3, prefetch, no_loads, 0); wait_lgkm0();
+            sub_step(R0, R1, t + 4, prefetch, no_loads, 0); wait_lgkm0();
+            sub_step(R1, R0, t + 5, prefetch, no_loads, 0); wait_lgkm0();
+            sub_step(R0, R1, t + 6, prefetch, no_loads, 0);
+            t += 4;
+        }
+        wait_lgkm0();
+        sub_step(R1, R0, t + 3, std::false_type{}, no_loads, 0);
+        wg_barrier();                                 // every wave is done with the operand tiles: LDS becomes staging
+        store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
     }
 }
 
 // ---- sparse INT8 over the lifted width: Y = X' . W'^T, W' packed 2:4 ---------------------------------
-// Sub-step = 64 lifted columns.  Token tiles (B) move in units of two sub-steps (128-byte rows), ring
-// of 3; packed weights (A) in units of one sub-step (8 KB values + 2 KB index words), ring of 6.
+// Sub-step = 64 lifted columns (one 32x32x64 sparse matrix instruction deep); unit = two sub-steps =
+// 128 lifted columns.  Ring of three units; a unit is a 32 KB token tile (128-byte rows), 16 KB of
+// weight values [panel 2][sub-step 2][fragment 4][lane 64][16 B] and 4 KB of index words
+// [panel 2][sub-step 2][lane 64][fragment 4][4 B], both in the order slide_decompose stores them.
+constexpr int S_RING = 3;
 constexpr int S_B_UNIT = BT * ROWB;                 // 32 KB
-constexpr int S_AV_UNIT = BO * 32;                  // 8 KB
-constexpr int S_AM_UNIT = BO * 8;                   // 2 KB
-constexpr int S_NB = 3, S_NA = 6;
-constexpr int S_AV_OFF = S_NB * S_B_UNIT;
-constexpr int S_AM_OFF = S_AV_OFF + S_NA * S_AV_UNIT;
-constexpr int S_LDS = S_AM_OFF + S_NA * S_AM_UNIT;  // 159744 bytes
+constexpr int S_AV_UNIT = BO * 64;                  // 16 KB
+constexpr int S_AM_UNIT = BO * 16;                  // 4 KB
+constexpr int S_AV_OFF = S_RING * S_B_UNIT;
+constexpr int S_AM_OFF = S_AV_OFF + S_RING * S_AV_UNIT;
+constexpr int S_LDS = S_AM_OFF + S_RING * S_AM_UNIT;  // 159744 bytes
 static_assert(S_LDS <= 160 * 1024 && EP_TILE_BYTES <= S_LDS && EP_TILE_BYTES <= D_LDS, "LDS budget");
-constexpr int S_LB = ROW_LOADS, S_LA = 1;           // direct loads per thread: B unit, A unit values (+1 index load in waves 0, 1)
+constexpr int S_LPU = ROW_LOADS + 2 + 2;            // direct loads per wavefront and unit: token rows, values, index words
 
 struct SparseFrags { v4i a[4]; v4i idx; v8i b[NBF]; };
 
-template <int DBG>
 __global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restrict__ XL, const float* __restrict__ s_x, const uint8_t* __restrict__ w_vals,
                                                          const uint8_t* __restrict__ w_meta, const float* __restrict__ s_w, int64_t M, int64_t O,
                                                          int64_t Kp, uint16_t* __restrict__ Y, int64_t ldy, int tiles_o, int tiles_t)
 {
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR
-    const int wo = wave & 1, wt = wave >> 1, grp = wave >> 2;
+    const int wo = wave & 1, wt = wave >> 1;
     const int n = lane & 31, qb = lane >> 5;
-    const int S = (int)(Kp / FRAG_K8);               // sub-steps; even because K' % 128 == 0
+    const int U = (int)(Kp / (2 * FRAG_K8));          // units
     const int64_t npanels = (O + PANEL - 1) / PANEL;
-    const bool meta_wave = wave < 2;                  // these two also fetch the index words (one panel each)
     int brow[NBF];
 #pragma unroll
     for (int bb = 0; bb < NBF; ++bb) brow[bb] = wt * (32 * NBF) + bb * 32 + n;
@@ -367,126 +370,118 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restri
     for (int round = 0; tile_of_round(round, tiles_o, tiles_t, to, tt); ++round) {
         const int64_t o_blk = (int64_t)to * BO, t_blk = (int64_t)tt * BT;
         RowTileLoader lb;
-        lb.init(XL, Kp, t_blk, M, wave, lane);
-        // packed weights: one sub-step of a 128-channel panel is 4 KB of values and 1 KB of index words,
-        // both contiguous.  Values: waves 0..3 fetch panel 2*to, waves 4..7 panel 2*to+1, 16 bytes a lane.
-        int64_t vpanel = (int64_t)to * 2 + (wave >> 2), mpanel = (int64_t)to * 2 + (wave & 1);
-        vpanel = vpanel < npanels ? vpanel : npanels - 1;
-        mpanel = mpanel < npanels ? mpanel : npanels - 1;
-        const uint8_t* av_base = w_vals + (vpanel * S * 256 + (wave & 3) * 64) * 16;    // wave-uniform
-        const uint8_t* am_base = w_meta + mpanel * S * 1024;
-        const uint32_t lane16 = lane * 16;
-        auto issue_a = [&](int s) {
-            if constexpr (!(DBG & 1)) {
-                lds_dma16(av_base + (int64_t)s * 4096 + lane16, smem + S_AV_OFF + (s % S_NA) * S_AV_UNIT + wave * 1024);
-                if (meta_wave) lds_dma16(am_base + (int64_t)s * 1024 + lane16, smem + S_AM_OFF + (s % S_NA) * S_AM_UNIT + wave * 1024);
+        lb.init(XL, Kp, (int64_t)tt * BT, M, wave, lane);
+        // Packed weights: per 128-channel panel the two sub-steps of a unit are contiguous, 8 KB of values
+        // and 2 KB of index words.  Waves 0..3 fetch panel 2*to, waves 4..7 panel 2*to+1 (clamped to the last
+        // panel; a clamped panel only feeds rows that are never stored): two 1 KB pieces of values (16 bytes
+        // a lane) and two 256-byte pieces of index words (4 bytes a lane) each.
+        int64_t panel = (int64_t)to * 2 + (wave >> 2);
+        panel = panel < npanels ? panel : npanels - 1;
+        const int piece = (wave & 3) * 2;
+        const uint8_t* av_src = w_vals + panel * U * 8192 + piece * 1024;     // wave-uniform
+        const uint8_t* am_src = w_meta + panel * U * 2048 + piece * 256;
+        uint8_t* av_dst = smem + S_AV_OFF + (wave >> 2) * 8192 + piece * 1024;
+        uint8_t* am_dst = smem + S_AM_OFF + (wave >> 2) * 2048 + piece * 256;
+        const uint32_t lane16 = lane * 16, lane4 = lane * 4;
+        // direct load number j (0..7) of this wavefront for unit u: token rows, values, token rows, index words, twice
+        auto issue_part = [&](int u, int slot, int j) {
+            {
+                const int half = j >> 2;
+                if (!(j & 1)) lb.issue_one(j >> 1, (int64_t)u * ROWB, smem + slot * S_B_UNIT, wave);
+                else if ((j & 3) == 1) lds_dma16(av_src + (int64_t)u * 8192 + half * 1024 + lane16, av_dst + slot * S_AV_UNIT + half * 1024);
+                else lds_dma4(am_src + (int64_t)u * 2048 + half * 256 + lane4, am_dst + slot * S_AM_UNIT + half * 256);
             }
         };
-        auto issue_b = [&](int unit) {
-            if constexpr (!(DBG & 1)) lb.issue((int64_t)unit * ROWB, smem + (unit % S_NB) * S_B_UNIT, wave);
+        auto issue = [&](int u, int slot) {
+#pragma unroll
+            for (int j = 0; j < S_LPU; ++j) issue_part(u, slot, j);
         };
 
         v16i acc[4][NBF];
         zero_acc(acc);
         SparseFrags R0, R1;
-        // one operand read of sub-step t: parts 0..3 weight values, 4 their index words, 5..8 the two
-        // halves of the two token fragments
-        auto read_part = [&](SparseFrags& R, int t, int part) {
-            if constexpr (!(DBG & 2)) {
-                if (part < 4) R.a[part] = *reinterpret_cast<const v4i*>(smem + S_AV_OFF + (t % S_NA) * S_AV_UNIT + ((wo * 4 + part) * 64 + lane) * 16);
-                else if (part == 4) R.idx = *reinterpret_cast<const v4i*>(smem + S_AM_OFF + (t % S_NA) * S_AM_UNIT + (wo * 64 + lane) * 16);
+        // one operand read of half h of the unit in ring slot `slot`: parts 0..3 weight values, 4 their
+        // index words, 5..8 the two halves of the two token fragments
+        auto read_part = [&](SparseFrags& R, int slot, int h, int part) {
+            {
+                if (part < 4) R.a[part] = *reinterpret_cast<const v4i*>(smem + S_AV_OFF + slot * S_AV_UNIT + ((wo * 2 + h) * 4 + part) * 1024 + lane16);
+                else if (part == 4) R.idx = *reinterpret_cast<const v4i*>(smem + S_AM_OFF + slot * S_AM_UNIT + (wo * 2 + h) * 1024 + lane16);
                 else {
-                    const int bb = (part - 5) >> 1, h = (part - 5) & 1;
-                    const v4i v = *tile_chunk(smem + ((t >> 1) % S_NB) * S_B_UNIT, brow[bb], 4 * (t & 1) + 2 * qb + h);
+                    const int bb = (part - 5) >> 1, hh = (part - 5) & 1;
+                    const v4i v = *tile_chunk(smem + slot * S_B_UNIT, brow[bb], 4 * h + 2 * qb + hh);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) R.b[bb][4 * h + e] = v[e];
+                    for (int e = 0; e < 4; ++e) R.b[bb][4 * hh + e] = v[e];
                 }
             }
         };
-        auto read_frags = [&](SparseFrags& R, int t) {
-#pragma unroll
-            for (int part = 0; part < 9; ++part) read_part(R, t, part);
-        };
-        // Matrix phase of sub-step t: the eight matrix instructions of sub-step t with the operand reads of
-        // sub-step t+1 placed one by one behind them.  A wavefront issues in order and a read waits for room
-        // in the LDS queue, which the three other SIMDs fill at the same time: reads bunched in front of the
-        // matrix instructions keep the matrix pipe idle for as long as the LDS takes to serve them.
-        auto matrix_phase = [&](const SparseFrags& cur, SparseFrags& nxt, int t, auto prefetch) {
-            if constexpr (!(DBG & 2)) {
+        // One sub-step: eight matrix instructions on `cur`, with the nine operand reads of the following
+        // sub-step (slot, h) placed one by one behind them.  A wavefront issues in order and an LDS read
+        // waits for room in the LDS queue, which the other SIMDs and the arriving direct loads fill too:
+        // reads bunched in front of the matrix instructions would idle the matrix pipe meanwhile.
+        // loads = 1 / 2: the first / second four direct loads of unit `lunit` (into ring slot lslot) are
+        // issued on the way, one behind every second matrix instruction: a burst of loads from all wavefronts
+        // fills the queue of the memory pipeline, and a wavefront whose load issue waits for room there
+        // issues no matrix instructions.
+        auto sub_step = [&](const SparseFrags& cur, SparseFrags& nxt, int slot, int h, auto prefetch, auto loads, int lunit, int lslot) {
+            {
                 __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int i = 0; i < 4 * NBF; ++i) {
                     acc[i / NBF][i % NBF] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(cur.a[i / NBF], cur.b[i % NBF], acc[i / NBF][i % NBF], cur.idx[i / NBF], 0, 0);
                     __builtin_amdgcn_sched_barrier(0);
+                    if constexpr (decltype(loads)::value > 0) {
+                        if (i & 1) { issue_part(lunit, lslot, 4 * (decltype(loads)::value - 1) + (i >> 1)); __builtin_amdgcn_sched_barrier(0); }
+                    }
                     if constexpr (decltype(prefetch)::value) {
-                        read_part(nxt, t + 1, i);
-                        if (i == 7) read_part(nxt, t + 1, 8);
+                        read_part(nxt, slot, h, i);
+                        if (i == 7) read_part(nxt, slot, h, 8);
                         __builtin_amdgcn_sched_barrier(0);
                     }
                 }
             }
         };
-        // Memory phase number xi of this wavefront (its partner on the SIMD is in a matrix phase): wait
-        // until this wave's loads of sub-step xi+2 have landed (two barriers later the first wavefront reads
-        // them), then request A sub-step xi+6 and, at odd xi, B unit (xi+1)/2+2 into ring slots whose last
-        // readers finished before the previous barrier.  In flight behind the awaited loads are the
-        // requests of the three previous memory phases: three A requests and one B request.
-        auto memory_phase = [&](int xi, bool steady) {
-            // (the waits below also cover this wave's operand reads of the matrix phase just finished, which
-            // must have returned before their ring slots are refilled after the next barrier)
-            if (xi + 2 < S) {
-                if (steady) { if (meta_wave) wait_vmcnt<3 * (S_LA + 1) + S_LB>(); else wait_vmcnt<3 * S_LA + S_LB>(); }
-                else wait_vmcnt<0>();
-            } else wait_lgkm0();
-            if ((xi & 1) && ((xi + 1) >> 1) + 2 < (S >> 1)) issue_b(((xi + 1) >> 1) + 2);
-            if (xi + 6 < S) issue_a(xi + 6);
-        };
 
-        // Prologue: sub-steps 0 and 1 first, then A2 | B1 A3 | A4 | B2 A5, the order later phases keep.
+        // The two wavefronts of a SIMD run freely against each other; the workgroup meets once per unit.
+        // Before that barrier a wavefront holds the operands of the unit's second sub-step in registers and
+        // has seen its own loads of the next unit land; after it nobody reads the unit's ring slot any more,
+        // so the unit three ahead is requested into it, and the next unit is visible to everybody.
         if (round > 0) wg_barrier();                  // epilogue staging of the previous tile has been read out
-        issue_b(0); issue_a(0); if (1 < S) issue_a(1);
-        if (2 < S) issue_a(2);
-        if (2 < S) issue_b(1); if (3 < S) issue_a(3);
-        if (4 < S) issue_a(4);
-        if (4 < S) issue_b(2); if (5 < S) issue_a(5);
-        const bool long_k = S >= 14;                  // short k: plain full waits everywhere
-        if (!long_k) wait_vmcnt<0>();
-        else if (meta_wave) wait_vmcnt<4 * (S_LA + 1) + 2 * S_LB>();
-        else wait_vmcnt<4 * S_LA + 2 * S_LB>();
-        wg_barrier();                                 // sub-steps 0 and 1 are published
-        int xi = 0;
-        read_frags(R0, 0);
+        issue(0, 0);
+        if (U > 1) issue(1, 1);
+        if (U > 2) issue(2, 2);
+        if (U > 2) wait_vmcnt<2 * S_LPU>(); else if (U > 1) wait_vmcnt<S_LPU>(); else wait_vmcnt<0>();
+        wg_barrier();                                 // unit 0 is published
+#pragma unroll
+        for (int part = 0; part < 9; ++part) read_part(R0, 0, 0, part);
         wait_lgkm0();
-        wg_barrier();                                 // everyone holds the operands of sub-step 0: its ring slot may be refilled
-        if (grp == 1) { memory_phase(xi, long_k); ++xi; wg_barrier(); }   // the second wavefront of every SIMD runs one phase behind
-        int t = 0;
-        if (long_k) {
-            for (; xi + 8 < S; t += 2) {              // every memory phase of the trip is a full one
-                if constexpr (DBG & 32) {
-                    long long c0 = __builtin_readcyclecounter();
-                    matrix_phase(R0, R1, t, std::true_type{}); long long c1 = __builtin_readcyclecounter();
-                    wg_barrier(); long long c2 = __builtin_readcyclecounter();
-                    memory_phase(xi++, true); long long c3 = __builtin_readcyclecounter();
-                    wg_barrier(); long long c4 = __builtin_readcyclecounter();
-                    if (blockIdx.x == 0 && round == 0 && lane == 0 && t >= 20 && t < 36) {
-                        long long* o = reinterpret_cast<long long*>(Y) + (wave * 8 + (t - 20) / 2) * 4;
-                        o[0] = c1 - c0; o[1] = c2 - c1; o[2] = c3 - c2; o[3] = c4 - c3;
-                    }
-                } else {
-                matrix_phase(R0, R1, t, std::true_type{});     wg_barrier(); memory_phase(xi++, true); wg_barrier();
-                }
-                matrix_phase(R1, R0, t + 1, std::true_type{}); wg_barrier(); memory_phase(xi++, true); wg_barrier();
-            }
+        constexpr std::integral_constant<int, 0> no_loads{};
+        constexpr std::integral_constant<int, 1> first_half{};
+        constexpr std::integral_constant<int, 2> second_half{};
+        constexpr std::true_type prefetch{};
+        int u = 0, slot = 0;
+        sub_step(R0, R1, slot, 1, prefetch, no_loads, 0, 0);
+        for (; u + 3 < U; ++u) {                      // units u+1 and u+2 are in flight, unit u+3 gets requested
+            const int nslot = slot == S_RING - 1 ? 0 : slot + 1;
+            wait_vmcnt<S_LPU>();                      // own loads of unit u+1 have landed, own reads of unit u have returned
+            wg_barrier();
+            sub_step(R1, R0, nslot, 0, prefetch, first_half, u + 3, slot);
+            wait_lgkm0();
+            sub_step(R0, R1, nslot, 1, prefetch, second_half, u + 3, slot);
+            slot = nslot;
         }
-        for (; t + 2 < S; t += 2) {
-            matrix_phase(R0, R1, t, std::true_type{});     wg_barrier(); memory_phase(xi++, false); wg_barrier();
-            matrix_phase(R1, R0, t + 1, std::true_type{}); wg_barrier(); memory_phase(xi++, false); wg_barrier();
+        for (; u + 1 < U; ++u) {                      // nothing left to request
+            const int nslot = slot == S_RING - 1 ? 0 : slot + 1;
+            wait_vmcnt<0>();
+            wg_barrier();
+            sub_step(R1, R0, nslot, 0, prefetch, no_loads, 0, 0);
+            wait_lgkm0();
+            sub_step(R0, R1, nslot, 1, prefetch, no_loads, 0, 0);
+            slot = nslot;
         }
-        matrix_phase(R0, R1, t, std::true_type{});      wg_barrier(); memory_phase(xi++, false); wg_barrier();
-        matrix_phase(R1, R0, t + 1, std::false_type{}); wg_barrier(); memory_phase(xi++, false); wg_barrier();
-        if (grp == 0) wg_barrier();                   // realign the two groups; every wave is done with the operand tiles
-        if constexpr (!(DBG & 4)) store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
-        else keep_alive(acc, Y);
+        wait_lgkm0();
+        sub_step(R1, R0, slot, 0, std::false_type{}, no_loads, 0, 0);
+        wg_barrier();                                 // every wave is done with the operand tiles: LDS becomes staging
+        store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
     }
 }
 
@@ -523,16 +518,9 @@ extern "C" ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
     const int grid = persistent_grid(tiles_o * tiles_t);
     if (grid <= 0) return SS_ERR_HIP;
-    const int dbg = getenv("SS_DBG") ? atoi(getenv("SS_DBG")) : 0;
-#define SS_LAUNCH_DENSE(D)                                                                                                              \
-    do {                                                                                                                                \
-        if (hipFuncSetAttribute((const void*)k_dense_i8<D>, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS) != hipSuccess) return SS_ERR_HIP; \
-        hipLaunchKernelGGL((k_dense_i8<D>), dim3(grid), dim3(G_THREADS), D_LDS, static_cast<hipStream_t>(stream),               \
-                           static_cast<const uint8_t*>(Xq), s_x, static_cast<const uint8_t*>(Wq), s_w, M, O, K, static_cast<uint16_t*>(Y), \
-                           ldy, tiles_o, tiles_t);                                                                                       \
-    } while (0)
-    if (dbg == 5) SS_LAUNCH_DENSE(5); else if (dbg == 6) SS_LAUNCH_DENSE(6); else if (dbg == 4) SS_LAUNCH_DENSE(4); else SS_LAUNCH_DENSE(0);
-#undef SS_LAUNCH_DENSE
+    if (hipFuncSetAttribute((const void*)k_dense_i8, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS) != hipSuccess) return SS_ERR_HIP;
+    hipLaunchKernelGGL(k_dense_i8, dim3(grid), dim3(G_THREADS), D_LDS, static_cast<hipStream_t>(stream), static_cast<const uint8_t*>(Xq), s_x,
+                       static_cast<const uint8_t*>(Wq), s_w, M, O, K, static_cast<uint16_t*>(Y), ldy, tiles_o, tiles_t);
     return launch_status();
 }
 
@@ -546,16 +534,10 @@ extern "C" ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, c
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
     const int grid = persistent_grid(tiles_o * tiles_t);
     if (grid <= 0) return SS_ERR_HIP;
-    const int dbg = getenv("SS_DBG") ? atoi(getenv("SS_DBG")) : 0;
-#define SS_LAUNCH_SPARSE(D)                                                                                                             \
-    do {                                                                                                                                \
-        if (hipFuncSetAttribute((const void*)k_sparse_i8<D>, hipFuncAttributeMaxDynamicSharedMemorySize, S_LDS) != hipSuccess) return SS_ERR_HIP; \
-        hipLaunchKernelGGL((k_sparse_i8<D>), dim3(grid), dim3(G_THREADS), S_LDS, static_cast<hipStream_t>(stream),              \
-                           static_cast<const uint8_t*>(X_lifted), s_x, static_cast<const uint8_t*>(w_vals),                               \
-                           static_cast<const uint8_t*>(w_meta), s_w, M, O, K_lifted, static_cast<uint16_t*>(Y), ldy, tiles_o, tiles_t);    \
-    } while (0)
-    if (dbg == 21) SS_LAUNCH_SPARSE(21); else if (dbg == 37) SS_LAUNCH_SPARSE(37); else if (dbg == 36) SS_LAUNCH_SPARSE(36); else if (dbg == 5) SS_LAUNCH_SPARSE(5); else if (dbg == 6) SS_LAUNCH_SPARSE(6); else if (dbg == 4) SS_LAUNCH_SPARSE(4); else SS_LAUNCH_SPARSE(0);
-#undef SS_LAUNCH_SPARSE
+    if (hipFuncSetAttribute((const void*)k_sparse_i8, hipFuncAttributeMaxDynamicSharedMemorySize, S_LDS) != hipSuccess) return SS_ERR_HIP;
+    hipLaunchKernelGGL(k_sparse_i8, dim3(grid), dim3(G_THREADS), S_LDS, static_cast<hipStream_t>(stream), static_cast<const uint8_t*>(X_lifted), s_x,
+                       static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, K_lifted, static_cast<uint16_t*>(Y), ldy,
+                       tiles_o, tiles_t);
     return launch_status();
 }
 
