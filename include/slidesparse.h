@@ -60,8 +60,10 @@ int64_t slide_lifted_k(int64_t K, int N);
 
 /* Byte sizes of the two buffers slide_decompose writes for an [O,K] weight matrix.
  * The packed layout is opaque (ordered for the sparse matrix instruction's operand and
- * index registers); rows are padded to a multiple of 128.  vals_bytes is about
- * (N-1)/N and meta_bytes (N-1)/(4N) (8-bit) of the dense weight bytes. */
+ * index registers); rows are padded to a multiple of 128.  With b = bytes per element,
+ * vals_bytes = Opad * K' * b / 2 ((N-1)/N of the dense weight bytes) and meta_bytes =
+ * Opad * K' * b / 8 (one 4-byte index word per 16 bytes of values; (N-1)/(4N) of dense).
+ * Requires K % 2N == 0 and K' * b % 128 == 0. */
 ss_status slide_packed_sizes(int64_t O, int64_t K, int N, ss_dtype dtype,
                              size_t* vals_bytes, size_t* meta_bytes);
 
@@ -80,7 +82,8 @@ ss_status slide_prune_quant(const void* W, ss_act_dtype in_dtype, int64_t O, int
  * rewritten as N-1 stride-2 windows of 4 by the greedy residual allocation (window order
  * g, l ascending; inside a window the first <=2 unused non-zeros in ascending position),
  * every window is stored as 2 values + two 2-bit positions, and the result is laid out
- * for slide_sparse_gemm.  Requires K % 2N == 0 and K' % 128 == 0 (SS_ERR_SHAPE otherwise).
+ * for slide_sparse_gemm.  Requires K % 2N == 0 and K' * sizeof(element) % 128 == 0
+ * (SS_ERR_SHAPE otherwise).
  * violations (nullable, device int32, must be zeroed by the caller): incremented once
  * per 2N block that holds more than 2N-2 non-zeros; output is unspecified for such blocks. */
 ss_status slide_decompose(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype,
@@ -107,14 +110,15 @@ ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_
  *   Y[m,o] = bf16( (fp32(acc[m,o]) * s_x[m]) * s_w[o] ),  acc = sum over K' of X' . W'
  * (SS_BF16: Y = bf16(acc), s_x and s_w ignored and may be NULL).  X_lifted[M,K_lifted]
  * dense row-major from act_lift_quant; w_vals/w_meta from slide_decompose for the same
- * O and K_lifted.  Y is bf16 [M,O] with row stride ldy (elements, >= O).
- * Requires K_lifted % 128 == 0. */
+ * O and K_lifted.  Y is bf16 [M,O] with row stride ldy (elements, >= O).  INT8 accumulates
+ * in int32 (exact), FP8 and BF16 in fp32 in the order of the matrix instructions.
+ * Requires K_lifted * sizeof(element) % 128 == 0 and 16-byte aligned operand pointers. */
 ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, const void* w_vals,
                             const void* w_meta, const float* s_w, int64_t M, int64_t O,
                             int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy, void* stream);
 
 /* Dense baseline at the original K with the same epilogue: Xq[M,K], Wq[O,K] row-major.
- * Requires K % 128 == 0. */
+ * Requires K * sizeof(element) % 128 == 0 and 16-byte aligned operand pointers. */
 ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq, const float* s_w,
                      int64_t M, int64_t O, int64_t K, ss_dtype dtype, void* Y, int64_t ldy,
                      void* stream);

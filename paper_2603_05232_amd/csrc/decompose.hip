@@ -1,6 +1,6 @@
 // slide_decompose: Sliding Window Decomposition (Alg. 2, greedy residual allocation) fused
 // with 2:4 compression, written output-oriented: one thread produces one lane's worth of
-// sparse-operand registers (16 stored values + one index word), so every store is coalesced.
+// sparse-operand registers (16 bytes of stored values + one index word), so every store is coalesced.
 // A thread re-runs the greedy over the few earlier windows of the same 2N block to recover
 // the carry; the block is at most 16 elements, so this costs a handful of integer ops.
 #include "ss_common.h"
@@ -65,11 +65,14 @@ __global__ __launch_bounds__(256) void k_decompose_canonical(const typename Elem
     if (violations && nnz > 2 * N - 2) atomicAdd(violations, 1);
 }
 
-// packed form for 8-bit operands: one thread per (panel, 64-column step, fragment, lane)
-__global__ __launch_bounds__(256) void k_decompose_packed8(const uint8_t* __restrict__ Wq, int64_t O, int K, int N, bool fp,
-                                                            uint4* __restrict__ vals, uint32_t* __restrict__ meta, int64_t nslots,
-                                                            int nsteps, int32_t* __restrict__ violations)
+// packed form: one thread per (panel, 64-byte step, fragment, lane)
+template <int ES>
+__global__ __launch_bounds__(256) void k_decompose_packed(const typename Elem<ES>::T* __restrict__ Wq, int64_t O, int K, int N, bool fp,
+                                                           uint4* __restrict__ vals, uint32_t* __restrict__ meta, int64_t nslots,
+                                                           int nsteps, int32_t* __restrict__ violations)
 {
+    typedef typename Elem<ES>::T T;
+    constexpr int NW = 8 / ES;                           // windows per lane
     const int64_t slot = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (slot >= nslots) return;
     const int lane = (int)(slot & 63);
@@ -80,17 +83,18 @@ __global__ __launch_bounds__(256) void k_decompose_packed8(const uint8_t* __rest
     const int64_t o = panel * PANEL + panel_row(f, lane & 31);
     const int qa = lane >> 5;
     uint32_t v[4] = {0, 0, 0, 0};
-    uint32_t m = 0x44444444u;                            // positions (0, 1) everywhere: an all-zero fragment
+    uint32_t m = ES == 1 ? 0x44444444u : 0x4444u;        // positions (0, 1) everywhere: an all-zero fragment
     if (o < O) {
         m = 0;
         int bad = 0;
 #pragma unroll
-        for (int w = 0; w < 8; ++w) {
-            const int j = step * (FRAG_K8 / 4) + step_window(qa, w);
+        for (int w = 0; w < NW; ++w) {
+            const int j = step * (2 * NW) + step_window<ES>(qa, w);
             const int g = j / (N - 1), l = j - g * (N - 1);
-            uint8_t v0, v1; uint32_t i0, i1; int nnz;
-            slide_window<1>(Wq + o * (int64_t)K, N, g, l, fp, v0, v1, i0, i1, nnz);
-            v[w >> 1] |= ((uint32_t)v0 | ((uint32_t)v1 << 8)) << (16 * (w & 1));
+            T v0, v1; uint32_t i0, i1; int nnz;
+            slide_window<ES>(Wq + o * (int64_t)K, N, g, l, fp, v0, v1, i0, i1, nnz);
+            if constexpr (ES == 1) v[w >> 1] |= ((uint32_t)v0 | ((uint32_t)v1 << 8)) << (16 * (w & 1));
+            else v[w] = (uint32_t)v0 | ((uint32_t)v1 << 16);
             m |= (i0 | (i1 << 2)) << (4 * w);
             bad += nnz > 2 * N - 2;
         }
@@ -117,12 +121,11 @@ extern "C" ss_status slide_packed_sizes(int64_t O, int64_t K, int N, ss_dtype dt
     ss_status st = check_decompose(O, K, N, dtype);
     if (st != SS_OK) return st;
     if (!vals_bytes || !meta_bytes) return SS_ERR_NULL;
-    const int64_t Kp = lifted_k(K, N);
-    if (Kp % KSTEP != 0) return SS_ERR_SHAPE;
-    if (dtype == SS_BF16) return SS_ERR_DTYPE;          // bf16 packing not built yet
+    const int64_t Kpb = lifted_k(K, N) * elem_size(dtype);    // bytes of a lifted row
+    if (Kpb % KSTEP != 0) return SS_ERR_SHAPE;
     const int64_t Opad = (O + PANEL - 1) / PANEL * PANEL;
-    *vals_bytes = (size_t)(Opad * (Kp / 2));
-    *meta_bytes = (size_t)(Opad * (Kp / 8));
+    *vals_bytes = (size_t)(Opad * (Kpb / 2));
+    *meta_bytes = (size_t)(Opad * (Kpb / 8));            // one 4-byte index word per 16 bytes of values
     return SS_OK;
 }
 
@@ -131,17 +134,21 @@ extern "C" ss_status slide_decompose(const void* Wq, int64_t O, int64_t K, int N
 {
     ss_status st = check_decompose(O, K, N, dtype);
     if (st != SS_OK) return st;
-    const int64_t Kp = lifted_k(K, N);
-    if (Kp % KSTEP != 0) return SS_ERR_SHAPE;
-    if (dtype == SS_BF16) return SS_ERR_DTYPE;
+    const int64_t Kpb = lifted_k(K, N) * elem_size(dtype);
+    if (Kpb % KSTEP != 0) return SS_ERR_SHAPE;
     if (O == 0) return SS_OK;
     if (!Wq || !w_vals || !w_meta) return SS_ERR_NULL;
     const int64_t npanels = (O + PANEL - 1) / PANEL;
-    const int nsteps = (int)(Kp / FRAG_K8);
+    const int nsteps = (int)(Kpb / FRAG_KB);
     const int64_t nslots = npanels * nsteps * FRAGS_PER_PANEL * 64;
-    hipLaunchKernelGGL(k_decompose_packed8, dim3((unsigned)((nslots + 255) / 256)), dim3(256), 0, static_cast<hipStream_t>(stream),
-                       static_cast<const uint8_t*>(Wq), O, (int)K, N, dtype == SS_FP8_E4M3, static_cast<uint4*>(w_vals),
-                       static_cast<uint32_t*>(w_meta), nslots, nsteps, violations);
+    const dim3 grid((unsigned)((nslots + 255) / 256)), block(256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (dtype == SS_BF16)
+        hipLaunchKernelGGL(k_decompose_packed<2>, grid, block, 0, s, static_cast<const uint16_t*>(Wq), O, (int)K, N, true,
+                           static_cast<uint4*>(w_vals), static_cast<uint32_t*>(w_meta), nslots, nsteps, violations);
+    else
+        hipLaunchKernelGGL(k_decompose_packed<1>, grid, block, 0, s, static_cast<const uint8_t*>(Wq), O, (int)K, N, dtype == SS_FP8_E4M3,
+                           static_cast<uint4*>(w_vals), static_cast<uint32_t*>(w_meta), nslots, nsteps, violations);
     return launch_status();
 }
 

@@ -3,8 +3,10 @@
 // Tile engine shared by both kernels: a persistent 512-thread workgroup (8 wavefronts, two per SIMD)
 // owns a 256 (output channels) x 256 (tokens) tile of Y at a time; wavefront (wo, wt) accumulates the
 // 128 x 64 sub-tile [wo*128, +128) x [wt*64, +64) as 4 x 2 blocks of a 32x32 matrix instruction.  The
-// weights are the A operand (sparse for slide_sparse_gemm: v_smfmac_i32_32x32x64_i8 takes 16 stored
-// bytes + one index word per lane), tokens are the B operand.
+// weights are the A operand (sparse for slide_sparse_gemm: the 32x32 sparse instructions take 16 bytes
+// of stored values + one index word per lane), tokens are the B operand.  All k extents are counted in
+// bytes of a row, so INT8, FP8 (e4m3) and BF16 share the kernels and differ in the matrix instruction,
+// the accumulator type and the epilogue.
 //
 // Data movement.  Operand tiles go HBM/L2 -> LDS with direct-to-LDS loads (no registers hold data in
 // flight) into rings of units; token rows are fetched as whole 128-byte lines and XOR-swizzled at
@@ -149,7 +151,8 @@ constexpr int EP_TILE_BYTES = 256 * 2 * EP_ROWB;    // 256 tokens x 2 channel pa
 
 // acc[f][b][r] of lane (n = lane & 31, h = lane >> 5) is channel o_base + 64 h + 16 f + r of token
 // t_base + 32 b + n.  `stage` is this wavefront's private 32 NBF rows of EP_ROWB bytes of LDS.
-template <typename ACC>
+// SCALED = false (bf16 operands): Y = bf16(acc), s_x and s_w are not touched.
+template <bool SCALED, typename ACC>
 __device__ inline void store_tile(const ACC (&acc)[4][NBF], const float* __restrict__ s_x, const float* __restrict__ s_w, uint16_t* __restrict__ Y,
                                   int64_t ldy, int64_t M, int64_t O, int64_t o_base, int64_t t_base, uint8_t* stage)
 {
@@ -159,7 +162,10 @@ __device__ inline void store_tile(const ACC (&acc)[4][NBF], const float* __restr
 #pragma unroll
     for (int f = 0; f < 4; ++f) {
         float sw[16];
-        if (sw_vec) {
+        if constexpr (!SCALED) {
+#pragma unroll
+            for (int i = 0; i < 16; ++i) sw[i] = 1.0f;
+        } else if (sw_vec) {
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const float4 v = reinterpret_cast<const float4*>(s_w + o0 + 16 * f)[i];
@@ -172,11 +178,16 @@ __device__ inline void store_tile(const ACC (&acc)[4][NBF], const float* __restr
 #pragma unroll
         for (int b = 0; b < NBF; ++b) {
             const int64_t tok = t_base + b * 32 + n;
-            const float sx = s_x[tok < M ? tok : M - 1];
             uint32_t w[8];
+            if constexpr (SCALED) {
+                const float sx = s_x[tok < M ? tok : M - 1];
 #pragma unroll
-            for (int q = 0; q < 8; ++q)
-                w[q] = pack_bf16x2(((float)acc[f][b][2 * q] * sx) * sw[2 * q], ((float)acc[f][b][2 * q + 1] * sx) * sw[2 * q + 1]);
+                for (int q = 0; q < 8; ++q)
+                    w[q] = pack_bf16x2(((float)acc[f][b][2 * q] * sx) * sw[2 * q], ((float)acc[f][b][2 * q + 1] * sx) * sw[2 * q + 1]);
+            } else {
+#pragma unroll
+                for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2((float)acc[f][b][2 * q], (float)acc[f][b][2 * q + 1]);
+            }
             uint4* dst = reinterpret_cast<uint4*>(stage + (b * 32 + n) * EP_ROWB + h * 128 + 32 * f);
             dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
             dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
@@ -218,22 +229,74 @@ template <typename ACC> __device__ inline void zero_acc(ACC (&acc)[4][NBF])
             for (int r = 0; r < 16; ++r) acc[f][b][r] = 0;
 }
 
-// ---- dense INT8: Y = Xq . Wq^T -------------------------------------------------------------------
-// Units of 128 k-bytes (4 sub-steps of the 32x32x32 instruction); rings of two units per operand.
+// ---- matrix instructions per operand type -----------------------------------------------------------
+// Sparse: one instruction is 32 channels x 32 tokens x 64 lifted bytes (A = 16 bytes of stored values + an
+// index word per lane, B = 32 bytes per lane).  Dense: DENSE_SUB k-bytes per instruction, A and B
+// DENSE_SUB / 2 bytes per lane; lane (row, q) holds the bytes [q DENSE_SUB / 2, (q + 1) DENSE_SUB / 2) of
+// its row within the instruction's k range, for both operands (measured: element e of A lane (i, q)
+// meets element e of B lane (n, q)).
+template <int DT> struct Mma;
+template <> struct Mma<SS_I8> {
+    typedef v16i acc_t;
+    typedef v4i dfrag_t;
+    static constexpr int DENSE_SUB = 32;
+    static constexpr bool SCALED = true;
+    __device__ static acc_t sparse(v4i a, v8i b, acc_t c, int idx) { return __builtin_amdgcn_smfmac_i32_32x32x64_i8(a, b, c, idx, 0, 0); }
+    __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
+};
+template <> struct Mma<SS_FP8_E4M3> {
+    typedef v16f acc_t;
+    typedef v8i dfrag_t;
+    static constexpr int DENSE_SUB = 64;
+    static constexpr bool SCALED = true;
+    __device__ static acc_t sparse(v4i a, v8i b, acc_t c, int idx) { return __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(a, b, c, idx, 0, 0); }
+    // format selectors 0 = e4m3 for both operands; block scales 0 = the unscaled form of the instruction
+    __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c) { return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0); }
+};
+template <> struct Mma<SS_BF16> {
+    typedef v16f acc_t;
+    typedef v4i dfrag_t;
+    static constexpr int DENSE_SUB = 32;
+    static constexpr bool SCALED = false;
+    __device__ static acc_t sparse(v4i a, v8i b, acc_t c, int idx)
+    {
+        return __builtin_amdgcn_smfmac_f32_32x32x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v16bf, b), c, idx, 0, 0);
+    }
+    __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
+    }
+};
+
+// operand reads [first, last) that go behind matrix instruction i of 8 when `parts` reads are spread evenly
+__device__ constexpr int part_begin(int i, int parts) { return (i * parts + 7) / 8; }
+
+constexpr std::integral_constant<int, 0> no_loads{};
+constexpr std::integral_constant<int, 1> first_half{};
+constexpr std::integral_constant<int, 2> second_half{};
+constexpr std::integral_constant<int, 0> even{};
+constexpr std::integral_constant<int, 1> odd{};
+
+// ---- dense: Y = Xq . Wq^T ----------------------------------------------------------------------------
+// Units of 128 k-bytes (128 / DENSE_SUB sub-steps); rings of two units per operand.  Kb = bytes per row.
 constexpr int D_UNIT = BO * ROWB;                   // 32 KB, same for A and B
 constexpr int D_LDS = EP_TILE_BYTES > 4 * D_UNIT ? EP_TILE_BYTES : 4 * D_UNIT;   // rings 128 KB; staging 136 KB
 
-struct DenseFrags { v4i a[4]; v4i b[NBF]; };
-
-__global__ __launch_bounds__(G_THREADS) void k_dense_i8(const uint8_t* __restrict__ Xq, const float* __restrict__ s_x, const uint8_t* __restrict__ Wq,
-                                                        const float* __restrict__ s_w, int64_t M, int64_t O, int64_t K, uint16_t* __restrict__ Y,
-                                                        int64_t ldy, int tiles_o, int tiles_t)
+template <int DT>
+__global__ __launch_bounds__(G_THREADS) void k_dense(const uint8_t* __restrict__ Xq, const float* __restrict__ s_x, const uint8_t* __restrict__ Wq,
+                                                     const float* __restrict__ s_w, int64_t M, int64_t O, int64_t Kb, uint16_t* __restrict__ Y,
+                                                     int64_t ldy, int tiles_o, int tiles_t)
 {
+    typedef Mma<DT> MM;
+    typedef typename MM::dfrag_t frag_t;
+    constexpr int SUB = MM::DENSE_SUB, NSUB = ROWB / SUB, RPF = SUB / 32;    // k-bytes, sub-steps per unit, 16-byte reads per fragment
+    constexpr int NPARTS = (4 + NBF) * RPF;
+    struct Frags { frag_t a[4]; frag_t b[2][NBF]; };   // weights single-buffered, tokens double-buffered by sub-step parity
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR
     const int wo = wave & 1, wt = wave >> 1;
     const int row = lane & 31, q = lane >> 5;
-    const int nunits = (int)(K / ROWB);
+    const int nunits = (int)(Kb / ROWB);
     int arow[4], brow[NBF];
 #pragma unroll
     for (int f = 0; f < 4; ++f) arow[f] = wo * 128 + panel_row(f, row);
@@ -244,102 +307,108 @@ __global__ __launch_bounds__(G_THREADS) void k_dense_i8(const uint8_t* __restric
     for (int round = 0; tile_of_round(round, tiles_o, tiles_t, to, tt); ++round) {
         const int64_t o_blk = (int64_t)to * BO, t_blk = (int64_t)tt * BT;
         RowTileLoader la, lb;
-        la.init(Wq, K, o_blk, O, wave, lane);
-        lb.init(Xq, K, t_blk, M, wave, lane);
+        la.init(Wq, Kb, o_blk, O, wave, lane);
+        lb.init(Xq, Kb, t_blk, M, wave, lane);
         // direct load number j (0..7) of this wavefront for a unit: weight and token rows alternate
         auto issue_part = [&](int unit, int j) {
-            {
-                if (j & 1) lb.issue_one(j >> 1, (int64_t)unit * ROWB, smem + 2 * D_UNIT + (unit & 1) * D_UNIT, wave);
-                else la.issue_one(j >> 1, (int64_t)unit * ROWB, smem + (unit & 1) * D_UNIT, wave);
-            }
+            if (j & 1) lb.issue_one(j >> 1, (int64_t)unit * ROWB, smem + 2 * D_UNIT + (unit & 1) * D_UNIT, wave);
+            else la.issue_one(j >> 1, (int64_t)unit * ROWB, smem + (unit & 1) * D_UNIT, wave);
         };
         auto issue = [&](int unit) {
 #pragma unroll
             for (int j = 0; j < 2 * ROW_LOADS; ++j) issue_part(unit, j);
         };
-        v16i acc[4][NBF];
+        typename MM::acc_t acc[4][NBF];
         zero_acc(acc);
-        DenseFrags R0, R1;
-        // one operand read of sub-step t: parts 0..3 are the weight fragments, 4..5 the token fragments
-        auto read_part = [&](DenseFrags& R, int t, int part) {
-            {
-                const uint8_t* sa = smem + ((t >> 2) & 1) * D_UNIT;
-                const int lc = 2 * (t & 3) + q;
-                if (part < 4) R.a[part] = *tile_chunk(sa, arow[part], lc);
-                else R.b[part - 4] = *tile_chunk(sa + 2 * D_UNIT, brow[part - 4], lc);
+        Frags R;
+        // one 16-byte operand read of sub-step t (t counts sub-steps of the whole k range): fragment
+        // part / RPF (0..3 weights, then tokens), piece part % RPF
+        auto read_part = [&](int t, int part, int buf) {
+            const uint8_t* sa = smem + ((t / NSUB) & 1) * D_UNIT;
+            const int frag = part / RPF, piece = part % RPF;
+            const int lc = (t % NSUB) * (SUB / 16) + q * RPF + piece;
+            const v4i v = frag < 4 ? *tile_chunk(sa, arow[frag], lc) : *tile_chunk(sa + 2 * D_UNIT, brow[frag - 4], lc);
+            frag_t& dst = frag < 4 ? R.a[frag] : R.b[buf][frag - 4];
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dst[4 * piece + e] = v[e];
+        };
+        // Sub-step t: its eight matrix instructions, with the operand reads of sub-step t+1 (if prefetch)
+        // and, for loads = 1 / 2, the first / second four direct loads of unit `lunit` placed one by one
+        // behind them.  A weight fragment is used by two consecutive instructions and refilled for the next
+        // sub-step right behind the second; the token fragments of the next sub-step go to the other buffer.
+        auto sub_step = [&](int t, auto parity, auto prefetch, auto loads, int lunit) {
+            constexpr int cb = decltype(parity)::value;     // t & 1, known at every call site
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int i = 0; i < 4 * NBF; ++i) {
+                acc[i / NBF][i % NBF] = MM::dense(R.a[i / NBF], R.b[cb][i % NBF], acc[i / NBF][i % NBF]);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (decltype(loads)::value > 0) {
+                    if (i & 1) { issue_part(lunit, 4 * (decltype(loads)::value - 1) + (i >> 1)); __builtin_amdgcn_sched_barrier(0); }
+                }
+                if constexpr (decltype(prefetch)::value) {
+                    if (i & 1) {
+#pragma unroll
+                        for (int piece = 0; piece < RPF; ++piece) read_part(t + 1, (i >> 1) * RPF + piece, cb ^ 1);
+                    } else {
+#pragma unroll
+                        for (int part = part_begin(i, NBF * RPF); part < part_begin(i + 2, NBF * RPF); ++part) read_part(t + 1, 4 * RPF + part, cb ^ 1);
+                    }
+                    __builtin_amdgcn_sched_barrier(0);
+                }
             }
         };
-        // Sub-step t: its eight matrix instructions, with the operand reads of sub-step t+1 placed one by
-        // one behind them.  A wavefront issues in order and an LDS read waits for room in the LDS queue,
-        // which the other SIMDs and the arriving direct loads fill too: reads bunched in front of the
-        // matrix instructions would idle the matrix pipe for as long as the LDS takes to accept them.
-        // loads = 1 / 2: the first / second four direct loads of unit `lunit` are issued on the way, one
-        // behind every second matrix instruction: a burst of loads from all wavefronts fills the queue of the
-        // memory pipeline, and a wavefront whose load issue waits for room there issues no matrix instructions.
-        auto sub_step = [&](const DenseFrags& cur, DenseFrags& nxt, int t, auto prefetch, auto loads, int lunit) {
-            {
-                __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                for (int i = 0; i < 4 * NBF; ++i) {
-                    acc[i / NBF][i % NBF] = __builtin_amdgcn_mfma_i32_32x32x32_i8(cur.a[i / NBF], cur.b[i % NBF], acc[i / NBF][i % NBF], 0, 0, 0);
-                    __builtin_amdgcn_sched_barrier(0);
-                    if constexpr (decltype(loads)::value > 0) {
-                        if (i & 1) { issue_part(lunit, 4 * (decltype(loads)::value - 1) + (i >> 1)); __builtin_amdgcn_sched_barrier(0); }
-                    }
-                    if constexpr (decltype(prefetch)::value) {
-                        if (i < 4 + NBF) { read_part(nxt, t + 1, i); __builtin_amdgcn_sched_barrier(0); }
-                    }
-                }
+        // the sub-steps of a unit except its last one; the first carries the second half of the loads of `lunit`
+        auto unit_head = [&](int t, auto loads, int lunit) {
+            static_assert(NSUB == 2 || NSUB == 4, "sub-steps per unit");
+            sub_step(t, even, std::true_type{}, loads, lunit);
+            if constexpr (NSUB == 4) {
+                wait_lgkm0(); sub_step(t + 1, odd, std::true_type{}, no_loads, 0);
+                wait_lgkm0(); sub_step(t + 2, even, std::true_type{}, no_loads, 0);
             }
         };
 
         // Unit u+2 is requested into the ring slot of unit u once every wavefront holds the operands of
-        // the last sub-step of unit u, and is awaited one unit later.
+        // the last sub-step of unit u (half of the loads ride on that sub-step, half on the next one), and
+        // is awaited before the last sub-step of unit u+1.
         if (round > 0) wg_barrier();                  // epilogue staging of the previous tile has been read out
         issue(0);
         if (nunits > 1) issue(1);
         if (nunits > 1) wait_vmcnt<2 * ROW_LOADS>(); else wait_vmcnt<0>();
         wg_barrier();                                 // unit 0 is published
 #pragma unroll
-        for (int part = 0; part < 4 + NBF; ++part) read_part(R0, 0, part);
+        for (int part = 0; part < NPARTS; ++part) read_part(0, part, 0);
         wait_lgkm0();
-        constexpr std::integral_constant<int, 0> no_loads{};
-        constexpr std::integral_constant<int, 1> first_half{};
-        constexpr std::integral_constant<int, 2> second_half{};
-        constexpr std::true_type prefetch{};
         int t = 0, u = 0;
-        sub_step(R0, R1, t, prefetch, no_loads, 0);     wait_lgkm0();
-        sub_step(R1, R0, t + 1, prefetch, no_loads, 0); wait_lgkm0();
-        sub_step(R0, R1, t + 2, prefetch, no_loads, 0);
-        for (; u + 2 < nunits; ++u, t += 4) {         // unit u+1 is in flight, unit u+2 gets requested
-            wait_vmcnt<0>();                          // unit u+1 has landed (and the reads of t+3 have returned)
+        unit_head(t, no_loads, 0);
+        for (; u + 2 < nunits; ++u, t += NSUB) {      // unit u+1 is in flight, unit u+2 gets requested
+            wait_vmcnt<0>();                          // unit u+1 has landed (and the reads of the last sub-step have returned)
             wg_barrier();                             // ... for every wavefront; nobody reads unit u's slot any more
-            sub_step(R1, R0, t + 3, prefetch, first_half, u + 2);  wait_lgkm0();
-            sub_step(R0, R1, t + 4, prefetch, second_half, u + 2); wait_lgkm0();
-            sub_step(R1, R0, t + 5, prefetch, no_loads, 0);        wait_lgkm0();
-            sub_step(R0, R1, t + 6, prefetch, no_loads, 0);
+            sub_step(t + NSUB - 1, odd, std::true_type{}, first_half, u + 2);
+            wait_lgkm0();
+            unit_head(t + NSUB, second_half, u + 2);
         }
         if (u + 1 < nunits) {                         // the last unit follows without further requests
             wait_vmcnt<0>();
             wg_barrier();
-            sub_step(R1, R0, t + 3, prefetch, no_loads, 0); wait_lgkm0();
-            sub_step(R0, R1, t + 4, prefetch, no_loads, 0); wait_lgkm0();
-            sub_step(R1, R0, t + 5, prefetch, no_loads, 0); wait_lgkm0();
-            sub_step(R0, R1, t + 6, prefetch, no_loads, 0);
-            t += 4;
+            sub_step(t + NSUB - 1, odd, std::true_type{}, no_loads, 0);
+            wait_lgkm0();
+            unit_head(t + NSUB, no_loads, 0);
+            t += NSUB;
         }
         wait_lgkm0();
-        sub_step(R1, R0, t + 3, std::false_type{}, no_loads, 0);
+        sub_step(t + NSUB - 1, odd, std::false_type{}, no_loads, 0);
         wg_barrier();                                 // every wave is done with the operand tiles: LDS becomes staging
-        store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
+        store_tile<MM::SCALED>(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
     }
 }
 
-// ---- sparse INT8 over the lifted width: Y = X' . W'^T, W' packed 2:4 ---------------------------------
-// Sub-step = 64 lifted columns (one 32x32x64 sparse matrix instruction deep); unit = two sub-steps =
-// 128 lifted columns.  Ring of three units; a unit is a 32 KB token tile (128-byte rows), 16 KB of
-// weight values [panel 2][sub-step 2][fragment 4][lane 64][16 B] and 4 KB of index words
+// ---- sparse over the lifted width: Y = X' . W'^T, W' packed 2:4 -------------------------------------
+// Sub-step = 64 lifted bytes (one sparse matrix instruction deep); unit = two sub-steps = 128 lifted
+// bytes.  Ring of three units; a unit is a 32 KB token tile (128-byte rows), 16 KB of weight values
+// [panel 2][sub-step 2][fragment 4][lane 64][16 B] and 4 KB of index words
 // [panel 2][sub-step 2][lane 64][fragment 4][4 B], both in the order slide_decompose stores them.
+// Kpb = bytes per lifted row.
 constexpr int S_RING = 3;
 constexpr int S_B_UNIT = BT * ROWB;                 // 32 KB
 constexpr int S_AV_UNIT = BO * 64;                  // 16 KB
@@ -350,17 +419,20 @@ constexpr int S_LDS = S_AM_OFF + S_RING * S_AM_UNIT;  // 159744 bytes
 static_assert(S_LDS <= 160 * 1024 && EP_TILE_BYTES <= S_LDS && EP_TILE_BYTES <= D_LDS, "LDS budget");
 constexpr int S_LPU = ROW_LOADS + 2 + 2;            // direct loads per wavefront and unit: token rows, values, index words
 
-struct SparseFrags { v4i a[4]; v4i idx; v8i b[NBF]; };
+// weight values single-buffered; index words and token fragments double-buffered by sub-step parity
+struct SparseFrags { v4i a[4]; v4i idx[2]; v8i b[2][NBF]; };
 
-__global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restrict__ XL, const float* __restrict__ s_x, const uint8_t* __restrict__ w_vals,
-                                                         const uint8_t* __restrict__ w_meta, const float* __restrict__ s_w, int64_t M, int64_t O,
-                                                         int64_t Kp, uint16_t* __restrict__ Y, int64_t ldy, int tiles_o, int tiles_t)
+template <int DT>
+__global__ __launch_bounds__(G_THREADS) void k_sparse(const uint8_t* __restrict__ XL, const float* __restrict__ s_x, const uint8_t* __restrict__ w_vals,
+                                                      const uint8_t* __restrict__ w_meta, const float* __restrict__ s_w, int64_t M, int64_t O,
+                                                      int64_t Kpb, uint16_t* __restrict__ Y, int64_t ldy, int tiles_o, int tiles_t)
 {
+    typedef Mma<DT> MM;
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;   // wave id in an SGPR
     const int wo = wave & 1, wt = wave >> 1;
     const int n = lane & 31, qb = lane >> 5;
-    const int U = (int)(Kp / (2 * FRAG_K8));          // units
+    const int U = (int)(Kpb / (2 * FRAG_KB));         // units
     const int64_t npanels = (O + PANEL - 1) / PANEL;
     int brow[NBF];
 #pragma unroll
@@ -370,7 +442,7 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restri
     for (int round = 0; tile_of_round(round, tiles_o, tiles_t, to, tt); ++round) {
         const int64_t o_blk = (int64_t)to * BO, t_blk = (int64_t)tt * BT;
         RowTileLoader lb;
-        lb.init(XL, Kp, (int64_t)tt * BT, M, wave, lane);
+        lb.init(XL, Kpb, t_blk, M, wave, lane);
         // Packed weights: per 128-channel panel the two sub-steps of a unit are contiguous, 8 KB of values
         // and 2 KB of index words.  Waves 0..3 fetch panel 2*to, waves 4..7 panel 2*to+1 (clamped to the last
         // panel; a clamped panel only feeds rows that are never stored): two 1 KB pieces of values (16 bytes
@@ -385,58 +457,50 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restri
         const uint32_t lane16 = lane * 16, lane4 = lane * 4;
         // direct load number j (0..7) of this wavefront for unit u: token rows, values, token rows, index words, twice
         auto issue_part = [&](int u, int slot, int j) {
-            {
-                const int half = j >> 2;
-                if (!(j & 1)) lb.issue_one(j >> 1, (int64_t)u * ROWB, smem + slot * S_B_UNIT, wave);
-                else if ((j & 3) == 1) lds_dma16(av_src + (int64_t)u * 8192 + half * 1024 + lane16, av_dst + slot * S_AV_UNIT + half * 1024);
-                else lds_dma4(am_src + (int64_t)u * 2048 + half * 256 + lane4, am_dst + slot * S_AM_UNIT + half * 256);
-            }
+            const int half = j >> 2;
+            if (!(j & 1)) lb.issue_one(j >> 1, (int64_t)u * ROWB, smem + slot * S_B_UNIT, wave);
+            else if ((j & 3) == 1) lds_dma16(av_src + (int64_t)u * 8192 + half * 1024 + lane16, av_dst + slot * S_AV_UNIT + half * 1024);
+            else lds_dma4(am_src + (int64_t)u * 2048 + half * 256 + lane4, am_dst + slot * S_AM_UNIT + half * 256);
         };
         auto issue = [&](int u, int slot) {
 #pragma unroll
             for (int j = 0; j < S_LPU; ++j) issue_part(u, slot, j);
         };
 
-        v16i acc[4][NBF];
+        typename MM::acc_t acc[4][NBF];
         zero_acc(acc);
-        SparseFrags R0, R1;
+        SparseFrags R;
         // one operand read of half h of the unit in ring slot `slot`: parts 0..3 weight values, 4 their
         // index words, 5..8 the two halves of the two token fragments
-        auto read_part = [&](SparseFrags& R, int slot, int h, int part) {
-            {
-                if (part < 4) R.a[part] = *reinterpret_cast<const v4i*>(smem + S_AV_OFF + slot * S_AV_UNIT + ((wo * 2 + h) * 4 + part) * 1024 + lane16);
-                else if (part == 4) R.idx = *reinterpret_cast<const v4i*>(smem + S_AM_OFF + slot * S_AM_UNIT + (wo * 2 + h) * 1024 + lane16);
-                else {
-                    const int bb = (part - 5) >> 1, hh = (part - 5) & 1;
-                    const v4i v = *tile_chunk(smem + slot * S_B_UNIT, brow[bb], 4 * h + 2 * qb + hh);
+        auto read_part = [&](int slot, int h, int part) {
+            if (part < 4) R.a[part] = *reinterpret_cast<const v4i*>(smem + S_AV_OFF + slot * S_AV_UNIT + ((wo * 2 + h) * 4 + part) * 1024 + lane16);
+            else if (part == 4) R.idx[h] = *reinterpret_cast<const v4i*>(smem + S_AM_OFF + slot * S_AM_UNIT + (wo * 2 + h) * 1024 + lane16);
+            else {
+                const int bb = (part - 5) >> 1, hh = (part - 5) & 1;
+                const v4i v = *tile_chunk(smem + slot * S_B_UNIT, brow[bb], 4 * h + 2 * qb + hh);
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) R.b[bb][4 * hh + e] = v[e];
-                }
+                for (int e = 0; e < 4; ++e) R.b[h][bb][4 * hh + e] = v[e];
             }
         };
-        // One sub-step: eight matrix instructions on `cur`, with the nine operand reads of the following
-        // sub-step (slot, h) placed one by one behind them.  A wavefront issues in order and an LDS read
-        // waits for room in the LDS queue, which the other SIMDs and the arriving direct loads fill too:
-        // reads bunched in front of the matrix instructions would idle the matrix pipe meanwhile.
-        // loads = 1 / 2: the first / second four direct loads of unit `lunit` (into ring slot lslot) are
-        // issued on the way, one behind every second matrix instruction: a burst of loads from all wavefronts
-        // fills the queue of the memory pipeline, and a wavefront whose load issue waits for room there
-        // issues no matrix instructions.
-        auto sub_step = [&](const SparseFrags& cur, SparseFrags& nxt, int slot, int h, auto prefetch, auto loads, int lunit, int lslot) {
-            {
-                __builtin_amdgcn_sched_barrier(0);
+        // Sub-step h^1 of a unit: eight matrix instructions, with the nine operand reads of the following
+        // sub-step (half h of the unit in `slot`) and, for loads = 1 / 2, the first / second four direct
+        // loads of unit `lunit` (into ring slot lslot) placed one by one behind them.  A weight fragment is
+        // used by two consecutive instructions and refilled right behind the second; index words and token
+        // fragments of the following sub-step go to the other buffer.
+        auto sub_step = [&](int slot, int h, auto prefetch, auto loads, int lunit, int lslot) {
+            const int c = h ^ 1;                      // buffers of the sub-step being computed
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int i = 0; i < 4 * NBF; ++i) {
-                    acc[i / NBF][i % NBF] = __builtin_amdgcn_smfmac_i32_32x32x64_i8(cur.a[i / NBF], cur.b[i % NBF], acc[i / NBF][i % NBF], cur.idx[i / NBF], 0, 0);
+            for (int i = 0; i < 4 * NBF; ++i) {
+                acc[i / NBF][i % NBF] = MM::sparse(R.a[i / NBF], R.b[c][i % NBF], acc[i / NBF][i % NBF], R.idx[c][i / NBF]);
+                __builtin_amdgcn_sched_barrier(0);
+                if constexpr (decltype(loads)::value > 0) {
+                    if (i & 1) { issue_part(lunit, lslot, 4 * (decltype(loads)::value - 1) + (i >> 1)); __builtin_amdgcn_sched_barrier(0); }
+                }
+                if constexpr (decltype(prefetch)::value) {
+                    if (i & 1) read_part(slot, h, i >> 1); else read_part(slot, h, 5 + (i >> 1));
+                    if (i == 1) read_part(slot, h, 4);
                     __builtin_amdgcn_sched_barrier(0);
-                    if constexpr (decltype(loads)::value > 0) {
-                        if (i & 1) { issue_part(lunit, lslot, 4 * (decltype(loads)::value - 1) + (i >> 1)); __builtin_amdgcn_sched_barrier(0); }
-                    }
-                    if constexpr (decltype(prefetch)::value) {
-                        read_part(nxt, slot, h, i);
-                        if (i == 7) read_part(nxt, slot, h, 8);
-                        __builtin_amdgcn_sched_barrier(0);
-                    }
                 }
             }
         };
@@ -452,36 +516,33 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse_i8(const uint8_t* __restri
         if (U > 2) wait_vmcnt<2 * S_LPU>(); else if (U > 1) wait_vmcnt<S_LPU>(); else wait_vmcnt<0>();
         wg_barrier();                                 // unit 0 is published
 #pragma unroll
-        for (int part = 0; part < 9; ++part) read_part(R0, 0, 0, part);
+        for (int part = 0; part < 9; ++part) read_part(0, 0, part);
         wait_lgkm0();
-        constexpr std::integral_constant<int, 0> no_loads{};
-        constexpr std::integral_constant<int, 1> first_half{};
-        constexpr std::integral_constant<int, 2> second_half{};
         constexpr std::true_type prefetch{};
         int u = 0, slot = 0;
-        sub_step(R0, R1, slot, 1, prefetch, no_loads, 0, 0);
+        sub_step(slot, 1, prefetch, no_loads, 0, 0);
         for (; u + 3 < U; ++u) {                      // units u+1 and u+2 are in flight, unit u+3 gets requested
             const int nslot = slot == S_RING - 1 ? 0 : slot + 1;
             wait_vmcnt<S_LPU>();                      // own loads of unit u+1 have landed, own reads of unit u have returned
             wg_barrier();
-            sub_step(R1, R0, nslot, 0, prefetch, first_half, u + 3, slot);
+            sub_step(nslot, 0, prefetch, first_half, u + 3, slot);
             wait_lgkm0();
-            sub_step(R0, R1, nslot, 1, prefetch, second_half, u + 3, slot);
+            sub_step(nslot, 1, prefetch, second_half, u + 3, slot);
             slot = nslot;
         }
         for (; u + 1 < U; ++u) {                      // nothing left to request
             const int nslot = slot == S_RING - 1 ? 0 : slot + 1;
             wait_vmcnt<0>();
             wg_barrier();
-            sub_step(R1, R0, nslot, 0, prefetch, no_loads, 0, 0);
+            sub_step(nslot, 0, prefetch, no_loads, 0, 0);
             wait_lgkm0();
-            sub_step(R0, R1, nslot, 1, prefetch, no_loads, 0, 0);
+            sub_step(nslot, 1, prefetch, no_loads, 0, 0);
             slot = nslot;
         }
         wait_lgkm0();
-        sub_step(R1, R0, slot, 0, std::false_type{}, no_loads, 0, 0);
+        sub_step(slot, 0, std::false_type{}, no_loads, 0, 0);
         wg_barrier();                                 // every wave is done with the operand tiles: LDS becomes staging
-        store_tile(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
+        store_tile<MM::SCALED>(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
     }
 }
 
@@ -502,12 +563,34 @@ static ss_status check_gemm(const void* X, const float* s_x, const void* W, cons
                             ss_dtype dtype, const void* Y, int64_t ldy)
 {
     if (dtype != SS_I8 && dtype != SS_FP8_E4M3 && dtype != SS_BF16) return SS_ERR_DTYPE;
-    if (M < 0 || O < 0 || K <= 0 || K % KSTEP != 0 || ldy < O || M > (1 << 24) || O > (1 << 24) || K > (1 << 24)) return SS_ERR_SHAPE;
-    if (dtype != SS_I8) return SS_ERR_DTYPE;          // fp8 / bf16 GEMMs not built yet
+    if (M < 0 || O < 0 || K <= 0 || (K * elem_size(dtype)) % KSTEP != 0 || ldy < O || M > (1 << 24) || O > (1 << 24) || K > (1 << 24))
+        return SS_ERR_SHAPE;
     if (M == 0 || O == 0) return SS_OK;
-    if (!X || !W || !Y || !s_x || !s_w) return SS_ERR_NULL;
+    if (!X || !W || !Y) return SS_ERR_NULL;
+    if (dtype != SS_BF16 && (!s_x || !s_w)) return SS_ERR_NULL;
     if (((uintptr_t)X & 15) || ((uintptr_t)W & 15)) return SS_ERR_SHAPE;
     return SS_OK;
+}
+
+template <int DT>
+static ss_status launch_dense(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, void* Y,
+                              int64_t ldy, int tiles_o, int tiles_t, int grid, hipStream_t stream)
+{
+    if (hipFuncSetAttribute((const void*)k_dense<DT>, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS) != hipSuccess) return SS_ERR_HIP;
+    hipLaunchKernelGGL((k_dense<DT>), dim3(grid), dim3(G_THREADS), D_LDS, stream, static_cast<const uint8_t*>(Xq), s_x,
+                       static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, tiles_o, tiles_t);
+    return launch_status();
+}
+
+template <int DT>
+static ss_status launch_sparse(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                               int64_t Kpb, void* Y, int64_t ldy, int tiles_o, int tiles_t, int grid, hipStream_t stream)
+{
+    if (hipFuncSetAttribute((const void*)k_sparse<DT>, hipFuncAttributeMaxDynamicSharedMemorySize, S_LDS) != hipSuccess) return SS_ERR_HIP;
+    hipLaunchKernelGGL((k_sparse<DT>), dim3(grid), dim3(G_THREADS), S_LDS, stream, static_cast<const uint8_t*>(XL), s_x,
+                       static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy,
+                       tiles_o, tiles_t);
+    return launch_status();
 }
 
 extern "C" ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t K,
@@ -518,10 +601,14 @@ extern "C" ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
     const int grid = persistent_grid(tiles_o * tiles_t);
     if (grid <= 0) return SS_ERR_HIP;
-    if (hipFuncSetAttribute((const void*)k_dense_i8, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS) != hipSuccess) return SS_ERR_HIP;
-    hipLaunchKernelGGL(k_dense_i8, dim3(grid), dim3(G_THREADS), D_LDS, static_cast<hipStream_t>(stream), static_cast<const uint8_t*>(Xq), s_x,
-                       static_cast<const uint8_t*>(Wq), s_w, M, O, K, static_cast<uint16_t*>(Y), ldy, tiles_o, tiles_t);
-    return launch_status();
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int64_t Kb = K * elem_size(dtype);
+    switch (dtype) {
+    case SS_I8: return launch_dense<SS_I8>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_FP8_E4M3: return launch_dense<SS_FP8_E4M3>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_BF16: return launch_dense<SS_BF16>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    }
+    return SS_ERR_DTYPE;
 }
 
 extern "C" ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w,
@@ -534,11 +621,14 @@ extern "C" ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, c
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
     const int grid = persistent_grid(tiles_o * tiles_t);
     if (grid <= 0) return SS_ERR_HIP;
-    if (hipFuncSetAttribute((const void*)k_sparse_i8, hipFuncAttributeMaxDynamicSharedMemorySize, S_LDS) != hipSuccess) return SS_ERR_HIP;
-    hipLaunchKernelGGL(k_sparse_i8, dim3(grid), dim3(G_THREADS), S_LDS, static_cast<hipStream_t>(stream), static_cast<const uint8_t*>(X_lifted), s_x,
-                       static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, K_lifted, static_cast<uint16_t*>(Y), ldy,
-                       tiles_o, tiles_t);
-    return launch_status();
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int64_t Kpb = K_lifted * elem_size(dtype);
+    switch (dtype) {
+    case SS_I8: return launch_sparse<SS_I8>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_FP8_E4M3: return launch_sparse<SS_FP8_E4M3>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_BF16: return launch_sparse<SS_BF16>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    }
+    return SS_ERR_DTYPE;
 }
 
 extern "C" const char* ss_status_string(ss_status s)

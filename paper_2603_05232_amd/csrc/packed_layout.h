@@ -1,7 +1,8 @@
 // The opaque packed weight layout shared by slide_decompose (writer) and slide_sparse_gemm
 // (reader).  It is ordered for the CDNA4 sparse matrix instructions so that one wavefront-wide
 // 16-byte load fills the sparse-operand registers of one instruction and one 4-byte load fills
-// its index register.
+// its index register.  Everything is laid out in bytes of the lifted row: a "step" is 64 lifted
+// bytes (64 columns of an 8-bit type, 32 of bf16), the depth of one sparse matrix instruction.
 //
 // 8-bit types use v_smfmac_*_32x32x64 (sparse operand A = 32 output channels x 64 lifted
 // columns, 16 stored values + 32 index bits per lane).  Measured operand semantics of that
@@ -12,6 +13,11 @@
 // gives B lane (n, qb) the 32 lifted columns [32 qb, 32 qb + 32) of token n within the
 // 64-column step, so stored value p of A lane (i, qa) belongs to window
 //     wi = 8 (w >> 2) + 4 qa + (w & 3),  w = p >> 1          (16 windows per step).
+// bf16 uses v_smfmac_f32_32x32x32_bf16 (8 stored values + 16 index bits per lane, same bit
+// positions [2p+1:2p]); measured: stored value p meets B element j = 8 qa + 4 ((p & 3) >> 1) + t
+// of B lane (n, qb = p >> 2).  With B lane (n, qb) holding the 16 lifted columns
+// [16 qb, 16 qb + 16) of the 32-column step, value p belongs to window
+//     wi = 4 (w >> 1) + 2 qa + (w & 1),  w = p >> 1          (8 windows per step).
 // The accumulator D[i][n] lives in lane n + 32 ((i >> 2) & 1), register (i & 3) + 4 (i >> 3).
 //
 // Output channels are grouped in panels of 128 = 4 fragments x 32 rows, and row i of fragment
@@ -23,16 +29,22 @@
 namespace ss {
 
 constexpr int FRAG_ROWS = 32;       // rows of one sparse fragment
-constexpr int FRAG_K8 = 64;         // lifted columns of one 8-bit sparse fragment
+constexpr int FRAG_KB = 64;         // lifted bytes (per row) of one sparse fragment = one step
 constexpr int FRAGS_PER_PANEL = 4;
 
 // output-channel offset inside a 128-row panel of row i (0..31) of fragment f (0..3)
 __host__ __device__ inline int panel_row(int f, int i) { return 64 * ((i >> 2) & 1) + 16 * f + 4 * (i >> 3) + (i & 3); }
-// window (0..15) inside a 64-column step held by lane half qa at window slot w (0..7)
-__host__ __device__ inline int step_window(int qa, int w) { return 8 * (w >> 2) + 4 * qa + (w & 3); }
+// window inside a step held by lane half qa at window slot w of the lane; a lane holds HW = 4 / ES
+// windows of each half of the step (ES = bytes per element: 8 slots of 16 windows, or 4 of 8)
+template <int ES> __host__ __device__ inline int step_window(int qa, int w)
+{
+    constexpr int HW = 4 / ES;
+    return 2 * HW * (w / HW) + HW * qa + (w % HW);
+}
 
 // slot of the 16-byte value group of (panel, step, fragment, lane); values are stored [panel][step][fragment][lane],
-// index words [panel][step][lane][fragment] so that one 16-byte read hands a lane the words of all four fragments
+// index words (4 bytes each, the upper half unused for bf16) [panel][step][lane][fragment], so that one 16-byte
+// read hands a lane the words of all four fragments
 __host__ __device__ inline int64_t frag_slot(int64_t panel, int64_t nsteps, int64_t step, int f, int lane)
 {
     return ((panel * nsteps + step) * FRAGS_PER_PANEL + f) * 64 + lane;

@@ -47,6 +47,10 @@ def test_packed_sizes(lib):
     assert v + m == int(0.9375 * 37888 * 3584)            # values 0.75x + index 0.1875x of dense bytes
     v, m = binding.slide_packed_sizes(130, 512, 4, "i8")    # rows padded to a multiple of 128
     assert v == 256 * 384
+    assert binding.slide_packed_sizes(512, 512, 4, "fp8") == (512 * 384, 512 * 96)
+    v, m = binding.slide_packed_sizes(512, 512, 4, "bf16")  # 2-byte values; one 4-byte index word per 16 value bytes
+    assert (v, m) == (512 * 384 * 2, 512 * 96 * 2)
+    assert binding.slide_packed_sizes(128, 128, 4, "bf16")[0] == 128 * 96 * 2   # K' = 192: 384 lifted bytes per row
     with pytest.raises(binding.SlideSparseError) as e:
         binding.slide_packed_sizes(512, 520, 4, "i8")       # K' = 780 is not a multiple of 128
     assert e.value.code == 3
@@ -76,6 +80,9 @@ def test_argument_errors_return_codes(lib):
     assert lib.dense_gemm(None, one, one, one, 16, 128, 128, 0, one, 128, None) == 1
     assert lib.dense_gemm(ctypes.c_void_p(8), one, one, one, 16, 128, 128, 0, one, 128, None) == 3
     assert lib.dense_gemm(one, one, one, one, 16, 128, 128, 9, one, 128, None) == 4
+    # bf16 rows are counted in bytes: K = 64 is a whole 128-byte line, K = 32 is not; scales may be NULL only for bf16
+    assert lib.dense_gemm(one, None, one, None, 16, 128, 32, 2, one, 128, None) == 3
+    assert lib.dense_gemm(one, None, one, None, 16, 128, 128, 0, one, 128, None) == 1
     # empty problems are fine and touch nothing
     assert lib.act_lift_quant(None, 0, 0, 64, 64, 4, 0, None, None, None) == 0
     assert lib.dense_gemm(None, None, None, None, 0, 128, 128, 0, None, 128, None) == 0

@@ -187,3 +187,72 @@ def test_gemm_strided_output_and_random_sparse_weights():
     binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8", out=buf2[:, :O])
     assert np.array_equal(bits16(buf2[:, :O].contiguous()), exp)
     assert torch.all(buf2[:, O:] == -1.0)
+
+
+# ------------------------------------------------------------------ FP8 / BF16 GEMMs
+def _float_gemm_check(Ybits, ref, dtype):
+    """Floating-point bar: max |Y - Y_ref| / (||Xd[m]||_2 ||Wd[o]||_2) <= 1e-2 with Xd, Wd the dequantised
+    operands and Y_ref the fp64 result before the bf16 rounding.  On top of it a bound derived from the
+    arithmetic (fp32 accumulation over K terms + one bf16 rounding), which a misplaced operand cannot meet:
+    |Y - Y_ref| <= 2^-8 |Y_ref| + K 2^-23 ||Xd[m]|| ||Wd[o]||."""
+    Xd = so.to_real(ref["Xq"], dtype)
+    Wd = so.to_real(ref["Wq"], dtype)
+    if dtype != "bf16":
+        Xd = Xd * ref["s_x"].astype(np.float64)[:, None]
+        Wd = Wd * ref["s_w"].astype(np.float64)[:, None]
+    Yref = Xd @ Wd.T
+    Y = so.bf16_to_f32(Ybits).astype(np.float64)
+    norm = np.linalg.norm(Xd, axis=1)[:, None] * np.linalg.norm(Wd, axis=1)[None, :]
+    norm = np.where(norm == 0, 1.0, norm)
+    err = np.abs(Y - Yref)
+    assert np.max(err / norm) <= 1e-2
+    K = Xd.shape[1]
+    assert np.all(err <= 2.0 ** -8 * np.abs(Yref) + K * 2.0 ** -23 * norm + 1e-30)
+
+
+@pytest.mark.parametrize("dtype", ["fp8", "bf16"])
+@pytest.mark.parametrize("N,M,O,K", [(4, 16, 512, 512),           # the anchor shape
+                                     (4, 300, 640, 1024),         # several tiles, ragged tokens and channels
+                                     (3, 257, 130, 768),          # one ragged panel
+                                     (5, 64, 256, 640),
+                                     (2, 40, 128, 256),           # native 2:4
+                                     (4, 1, 384, 512)])           # a single token
+def test_sparse_and_dense_gemm_float(dtype, N, M, O, K):
+    X = synth.activations(M, K, seed=M + O)
+    W = synth.weights(O, K, seed=M + O)
+    if M > 2:
+        X[1] = 0.0                                               # an all-zero token
+    ref = so.linear_reference(X, W, N, dtype)
+    Xd, Wd = dev(X), dev(W)
+    Wq, s_w = binding.slide_prune_quant(Wd, N, dtype)
+    assert np.array_equal(from_dev_q(Wq, dtype), ref["Wq"])
+    w_vals, w_meta, viol = binding.slide_decompose(Wq, N, dtype, count_violations=True)
+    XL, s_x = binding.act_lift_quant(Xd, N, dtype)
+    Y = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype)
+    assert int(host(viol)[0]) == 0
+    _float_gemm_check(bits16(Y), ref, dtype)
+    Xq, s_x2 = binding.act_lift_quant(Xd, 2, dtype)
+    assert np.array_equal(from_dev_q(Xq, dtype), ref["Xq"])
+    Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype)
+    _float_gemm_check(bits16(Yd), ref, dtype)
+    # small integers make every product and partial sum exact in fp32: then both kernels must return
+    # exactly the rounded exact result, whatever their summation order
+    rng = np.random.default_rng(K + M)
+    Xi = rng.integers(-4, 5, size=(M, K)).astype(np.float32)
+    Wi = so.prune_2n(rng.integers(-4, 5, size=(O, K)).astype(np.float32), N)
+    if dtype == "fp8":
+        Xq_i, Wq_i = so.fp8_e4m3_encode(Xi), so.fp8_e4m3_encode(Wi)
+        sx = np.ones(M, np.float32); sw = np.ones(O, np.float32)
+    else:
+        Xq_i, Wq_i = so.bf16_bits(Xi), so.bf16_bits(Wi)
+        sx = sw = None
+    exp = so.epilogue(so.gemm_exact(Xq_i, Wq_i, dtype), sx, sw, dtype)
+    Wq_t = to_dev_q(Wq_i, dtype)
+    w_vals, w_meta = binding.slide_decompose(Wq_t, N, dtype)
+    XL_t = to_dev_q(so.lift(Xq_i, N), dtype)
+    sxd = None if sx is None else dev(sx)
+    swd = None if sw is None else dev(sw)
+    Ys = binding.slide_sparse_gemm(XL_t, sxd, w_vals, w_meta, swd, O, dtype)
+    assert np.array_equal(bits16(Ys), exp)
+    Yd = binding.dense_gemm(to_dev_q(Xq_i, dtype), sxd, Wq_t, swd, dtype)
+    assert np.array_equal(bits16(Yd), exp)
