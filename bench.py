@@ -23,6 +23,12 @@ sys.path.insert(0, ROOT)
 PEAK_INT8_DENSE_TOPS = 5033.0      # MI355X published dense INT8; v_smfmac runs at the same MAC rate with 2x the K
 PEAK_INT8_SPARSE_TOPS = 2 * PEAK_INT8_DENSE_TOPS
 PEAK_HBM_GBS = 8000.0
+# HBM traffic of the sparse GEMM kernel per launch (mean over the four layer launches of a step), from the
+# FETCH_SIZE and WRITE_SIZE counters of two rocprofv3 --pmc runs of this script, each scaled by what the same
+# counter reads for the 256 MiB elementwise copy of --copy-calibration (FETCH_SIZE x 1.9997, WRITE_SIZE x 1.0);
+# summary and commands in profiles/gemm_qwen7b_m8192_int8_hbm_traffic.txt.  Bytes per launch:
+# 1.054e9 fetched (L2 misses, including those the memory-side cache serves) + 2.035e8 written.
+SPARSE_GEMM_TRAFFIC = 1.2573e9
 N_PATTERN = 4                      # 6:8
 M_TOKENS = 8192
 
@@ -34,7 +40,10 @@ def parse():
     ap.add_argument("--warmup", type=int, default=25)
     ap.add_argument("--tokens", type=int, default=M_TOKENS)
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-sample-tokens", type=int, default=2048)
+    ap.add_argument("--copy-calibration", action="store_true",
+                    help="also run a plain elementwise copy of known size (256 MiB read + 256 MiB written per launch), the "
+                         "yardstick that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script")
+    ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--cpu-sample-channels", type=int, default=8192)
     return ap.parse_args()
 
@@ -142,6 +151,14 @@ def main():
                 acc[i, 1] += ev[i][1].elapsed_time(ev[i][2])
         return acc / reps
 
+    if args.copy_calibration:
+        src = torch.zeros(64 * 1024 * 1024, dtype=torch.int32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(5):
+            torch.add(src, 1, out=dst)
+        torch.cuda.synchronize()
+        del src, dst
+
     t_sparse = timed(sparse_step)
     t_dense = timed(dense_step)
     reps = max(5, min(args.steps, 50))
@@ -185,13 +202,13 @@ def main():
         "sparse_equals_dense_bitwise": same,
         "per_layer": per_layer,
         "roofline": {"bound": "mfma", "achieved": executed_tops, "peak": PEAK_INT8_DENSE_TOPS, "unit": "TFLOP/s",
-                     "frac": executed_tops / PEAK_INT8_DENSE_TOPS, "traffic": None,
-                     "kernel": "k_sparse_i8 (slide_sparse_gemm), mean over the four layer launches",
+                     "frac": executed_tops / PEAK_INT8_DENSE_TOPS, "traffic": SPARSE_GEMM_TRAFFIC,
+                     "kernel": "ss::k_sparse<0> (slide_sparse_gemm, INT8), mean over the four layer launches of a step",
                      "note": "INT8 ops; achieved = executed MACs x 2 = M*O*K_lifted per launch / HIP-event duration; "
                              "identical to hardware-counted 2*M*O*K_lifted against the 2x sparse peak"},
         "roofline_dense": {"bound": "mfma", "achieved": useful_ops / (dgemm_ms * 1e-3) * 1e-12, "peak": PEAK_INT8_DENSE_TOPS,
                            "unit": "TFLOP/s", "frac": useful_ops / (dgemm_ms * 1e-3) * 1e-12 / PEAK_INT8_DENSE_TOPS,
-                           "kernel": "k_dense_i8 (dense_gemm)"},
+                           "kernel": "ss::k_dense<0> (dense_gemm, INT8)"},
         "roofline_lift": {"bound": "hbm", "achieved": lift_bytes / (lift_ms * 1e-3) * 1e-9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                           "frac": lift_bytes / (lift_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, "kernel": "k_act_lift_quant (fp32 in, int8 out)"},
     }
