@@ -1,0 +1,87 @@
+"""GPU parity at the full sizes of the benchmark configurations, in the launch configuration bench.py
+times: the whole hot path runs on the full tensors, and the CPU oracle recomputes a random sample of
+output elements (whole tokens x whole channels are independent of the rest: quantisation is per token
+and per channel, pruning per channel).  INT8 must be bit-exact; in addition the sparse and the dense
+path must agree on every element of the full output."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slide_oracle as so
+from paper_2603_05232_amd import binding, synth
+from test_gpu_parity import dev, host, bits16, from_dev_q, _float_gemm_check
+
+pytestmark = pytest.mark.gpu
+N_SAMPLE = 96
+
+
+def _run_and_sample(M, K, O, N, dtype, seed):
+    X = synth.activations(M, K, seed)
+    W = synth.weights(O, K, seed)
+    Xd, Wd = dev(X), dev(W)
+    Wq, s_w = binding.slide_prune_quant(Wd, N, dtype)
+    del Wd
+    w_vals, w_meta, viol = binding.slide_decompose(Wq, N, dtype, count_violations=True)
+    XL, s_x = binding.act_lift_quant(Xd, N, dtype)
+    Y = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype)
+    Y2 = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype)
+    Xq, s_x2 = binding.act_lift_quant(Xd, 2, dtype)
+    Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype)
+    assert int(host(viol)[0]) == 0
+    assert torch.equal(Y, Y2)                                    # deterministic from launch to launch
+    rng = np.random.default_rng(seed + 12345)
+    rows = np.sort(rng.choice(M, size=min(M, N_SAMPLE), replace=False))
+    cols = np.sort(rng.choice(O, size=min(O, N_SAMPLE), replace=False))
+    if M > 1:
+        rows[-1] = M - 1                                         # the last token and channel: tile tails
+    cols[-1] = O - 1
+    ref = so.linear_reference(X[rows], W[cols], N, dtype)
+    ri, ci = torch.from_numpy(rows).to(Y.device), torch.from_numpy(cols).to(Y.device)
+    sample = lambda T: bits16(T[ri][:, ci].contiguous())
+    # operands the sample depends on
+    assert np.array_equal(from_dev_q(Wq[ci].contiguous(), dtype), ref["Wq"])
+    assert np.array_equal(from_dev_q(Xq[ri].contiguous(), dtype), ref["Xq"])
+    assert np.array_equal(from_dev_q(XL[ri].contiguous(), dtype), so.lift(ref["Xq"], N))
+    return Y, Yd, sample, ref
+
+
+@pytest.mark.parametrize("name,K,O", synth.QWEN25_7B)
+def test_qwen25_7b_int8_m8192(name, K, O):
+    Y, Yd, sample, ref = _run_and_sample(8192, K, O, 4, "i8", seed=len(name))
+    assert np.array_equal(sample(Y), ref["Y"])
+    assert torch.equal(Y, Yd)
+
+
+@pytest.mark.parametrize("N,K,O", synth.PATTERN_SWEEP)
+def test_pattern_sweep_int8_m8192(N, K, O):
+    Y, Yd, sample, ref = _run_and_sample(8192, K, O, N, "i8", seed=N)
+    assert np.array_equal(sample(Y), ref["Y"])
+    assert torch.equal(Y, Yd)
+
+
+@pytest.mark.parametrize("name,K,O", synth.LLAMA3_8B)
+def test_llama3_8b_block_int8_m4096(name, K, O):
+    Y, Yd, sample, ref = _run_and_sample(4096, K, O, 4, "i8", seed=10 + len(name))
+    assert np.array_equal(sample(Y), ref["Y"])
+    assert torch.equal(Y, Yd)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("M", [1, 16, 128])
+@pytest.mark.parametrize("name,K,O", [synth.QWEN25_7B[0], synth.QWEN25_7B[3]])
+def test_qwen25_7b_small_m(dtype, M, name, K, O):
+    Y, Yd, sample, ref = _run_and_sample(M, K, O, 4, dtype, seed=M)
+    if dtype == "i8":
+        assert np.array_equal(sample(Y), ref["Y"])
+        assert torch.equal(Y, Yd)
+    else:
+        _float_gemm_check(sample(Y), ref, dtype)
+        _float_gemm_check(sample(Yd), ref, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["fp8", "bf16"])
+@pytest.mark.parametrize("name,K,O", [synth.QWEN25_7B[0], synth.QWEN25_7B[3]])
+def test_qwen25_7b_float_m8192(dtype, name, K, O):
+    Y, Yd, sample, ref = _run_and_sample(8192, K, O, 4, dtype, seed=7)
+    _float_gemm_check(sample(Y), ref, dtype)
+    _float_gemm_check(sample(Yd), ref, dtype)
