@@ -43,6 +43,10 @@ def parse():
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise copy of known size (256 MiB read + 256 MiB written per launch), the "
                          "yardstick that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script")
+    ap.add_argument("--sweep", choices=["dtypes_m", "patterns", "llama_block"], default=None,
+                    help="instead of the headline step, time one of the other benchmark configurations and print its table "
+                         "as one JSON line: dtypes_m = INT8/FP8/BF16 at M in {1,16,128,8192} on the Qwen2.5-7B shapes; "
+                         "patterns = 4:6, 6:8, 8:10 at M=8192 INT8; llama_block = Llama-3-8B linears at M=4096, 6:8 INT8")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--cpu-sample-channels", type=int, default=8192)
     return ap.parse_args()
@@ -78,6 +82,54 @@ def cpu_baseline(layers, n_tok, n_ch):
             "seconds": dt}
 
 
+def sweep(args, torch, binding, synth, dev):
+    """Times lift + sparse GEMM against quantise + dense GEMM for every case of one configuration."""
+    if args.sweep == "dtypes_m":
+        cases = [(dt, M, 4, name, K, O) for dt in ("i8", "fp8", "bf16") for M in (1, 16, 128, 8192) for name, K, O in synth.QWEN25_7B]
+    elif args.sweep == "patterns":
+        cases = [("i8", 8192, N, f"{2 * N - 2}:{2 * N}", K, O) for N, K, O in synth.PATTERN_SWEEP]
+    else:
+        cases = [("i8", 4096, 4, name, K, O) for name, K, O in synth.LLAMA3_8B]
+    esize = {"i8": 1, "fp8": 1, "bf16": 2}
+    peak = {"i8": PEAK_INT8_DENSE_TOPS, "fp8": PEAK_INT8_DENSE_TOPS, "bf16": PEAK_INT8_DENSE_TOPS / 2}
+    rows = []
+    for dt, M, N, name, K, O in cases:
+        X = torch.from_numpy(synth.activations(M, K, seed=1)).to(dev)
+        W = torch.from_numpy(synth.weights(O, K, seed=1)).to(dev)
+        Wq, s_w = binding.slide_prune_quant(W, N, dt)
+        w_vals, w_meta = binding.slide_decompose(Wq, N, dt)
+        del W
+        Kp = binding.slide_lifted_k(K, N)
+        XL, s_x = binding.act_lift_quant(X, N, dt)
+        Xq, s_xd = binding.act_lift_quant(X, 2, dt)
+        Y = torch.empty((M, O), dtype=torch.bfloat16, device=dev)
+        fns = {"lift": lambda: binding.act_lift_quant(X, N, dt, out=XL, s_x=s_x),
+               "sparse": lambda: binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dt, out=Y),
+               "quant": lambda: binding.act_lift_quant(X, 2, dt, out=Xq, s_x=s_xd),
+               "dense": lambda: binding.dense_gemm(Xq, s_xd, Wq, s_w, dt, out=Y)}
+        t = {}
+        for k, fn in fns.items():
+            for _ in range(args.warmup):
+                fn()
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(args.steps):
+                fn()
+            e1.record()
+            torch.cuda.synchronize()
+            t[k] = e0.elapsed_time(e1) / args.steps
+        b = esize[dt]
+        sparse_bytes = O * Kp * b * 0.625 + M * Kp * b + 2 * M * O     # packed weights + lifted tokens + output
+        rows.append({"dtype": dt, "M": M, "pattern": f"{2 * N - 2}:{2 * N}", "layer": name, "K": K, "O": O, "K_lifted": Kp,
+                     "lift_ms": t["lift"], "sparse_gemm_ms": t["sparse"], "quant_ms": t["quant"], "dense_gemm_ms": t["dense"],
+                     "gemm_speedup": t["dense"] / t["sparse"], "layer_speedup": (t["quant"] + t["dense"]) / (t["lift"] + t["sparse"]),
+                     "sparse_frac_of_sparse_peak": 2.0 * M * O * Kp / (t["sparse"] * 1e-3) * 1e-12 / (2 * peak[dt]),
+                     "dense_frac_of_dense_peak": 2.0 * M * O * K / (t["dense"] * 1e-3) * 1e-12 / peak[dt],
+                     "sparse_gemm_algorithmic_GBps": sparse_bytes / (t["sparse"] * 1e-3) * 1e-9})
+        del X, Wq, w_vals, w_meta, XL, Xq, Y
+    print(json.dumps({"sweep": args.sweep, "steps": args.steps, "warmup": args.warmup, "speedup_bound": "N/(N-1)", "cases": rows}))
+
+
 def main():
     args = parse()
     if args.gpus != 1:
@@ -91,6 +143,9 @@ def main():
         sys.exit(1)
     binding.load()
     dev = torch.device("cuda:0")
+    if args.sweep:
+        sweep(args, torch, binding, synth, dev)
+        return
     M = args.tokens
     layers = synth.QWEN25_7B
     N = N_PATTERN
@@ -109,6 +164,11 @@ def main():
                   s_x=torch.empty((M,), dtype=torch.float32, device=dev), s_xd=torch.empty((M,), dtype=torch.float32, device=dev),
                   Y=torch.empty((M, O), dtype=torch.bfloat16, device=dev), Yd=torch.empty((M, O), dtype=torch.bfloat16, device=dev))
         assert int(viol.item()) == 0
+        # native 2:4 weights (N = 2) of the same layer: the upper bound the lifted path is measured against
+        W = torch.from_numpy(synth.weights(O, K, seed=li)).to(dev)
+        Wq24, st["s_w24"] = binding.slide_prune_quant(W, 2, "i8")
+        st["w_vals24"], st["w_meta24"] = binding.slide_decompose(Wq24, 2, "i8")
+        del W, Wq24
         state.append(st)
     torch.cuda.synchronize()
 
@@ -126,6 +186,14 @@ def main():
             binding.act_lift_quant(s["X"], 2, "i8", out=s["Xq"], s_x=s["s_xd"])
             if ev: ev[i][1].record()
             binding.dense_gemm(s["Xq"], s["s_xd"], s["Wq"], s["s_w"], "i8", out=s["Yd"])
+            if ev: ev[i][2].record()
+
+    def native24_step(ev=None):
+        for i, s in enumerate(state):
+            if ev: ev[i][0].record()
+            binding.act_lift_quant(s["X"], 2, "i8", out=s["Xq"], s_x=s["s_xd"])
+            if ev: ev[i][1].record()
+            binding.slide_sparse_gemm(s["Xq"], s["s_xd"], s["w_vals24"], s["w_meta24"], s["s_w24"], s["O"], "i8", out=s["Yd"])
             if ev: ev[i][2].record()
 
     def timed(step_fn):
@@ -167,6 +235,8 @@ def main():
 
     # parity spot check inside the bench: sparse and dense paths must agree bit for bit
     same = all(bool(torch.equal(s["Y"], s["Yd"])) for s in state)
+    k_24 = per_kernel(native24_step, reps)           # (overwrites Yd; after the comparison)
+    g24_ms = float(k_24[:, 1].sum())
 
     hw_ops = sum(2.0 * M * s["O"] * s["Kp"] for s in state)          # what a "sparse peak" figure counts
     useful_ops = sum(2.0 * M * s["O"] * s["K"] for s in state)
@@ -197,6 +267,10 @@ def main():
         "speedup_gemm_vs_own_dense": dgemm_ms / gemm_ms,
         "speedup_layer_vs_own_dense": t_dense / t_sparse,
         "speedup_bound_N_over_N_minus_1": N / (N - 1.0),
+        # Sec. 5 efficiency: measured speed-up over what native 2:4 on the same kernels predicts, S_2:4 / gamma
+        "native_2_4_gemm_ms": g24_ms, "speedup_native_2_4_vs_own_dense": dgemm_ms / g24_ms,
+        "efficiency_vs_native_2_4": (dgemm_ms / gemm_ms) / ((dgemm_ms / g24_ms) / (2.0 - 2.0 / N)),
+        "lift_overhead_vs_quant_only": lift_ms / quant_ms,
         "paper_context": "1.33x end-to-end at 6:8 INT8 on A100, Qwen2.5-7B prefill M=8192 (other hardware, not a target)",
         "dense_ms_per_step": t_dense * 1e3, "lift_ms": lift_ms, "quant_only_ms": quant_ms,
         "sparse_equals_dense_bitwise": same,

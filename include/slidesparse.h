@@ -110,7 +110,7 @@ ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_
  *   Y[m,o] = bf16( (fp32(acc[m,o]) * s_x[m]) * s_w[o] ),  acc = sum over K' of X' . W'
  * (SS_BF16: Y = bf16(acc), s_x and s_w ignored and may be NULL).  X_lifted[M,K_lifted]
  * dense row-major from act_lift_quant; w_vals/w_meta from slide_decompose for the same
- * O and K_lifted.  Y is bf16 [M,O] with row stride ldy (elements, >= O).  INT8 accumulates
+ * O and K_lifted.  Y is bf16 [M,O] with row stride ldy (elements, O <= ldy < 2^22).  INT8 accumulates
  * in int32 (exact), FP8 and BF16 in fp32 in the order of the matrix instructions.
  * Requires K_lifted * sizeof(element) % 128 == 0 and 16-byte aligned operand pointers. */
 ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, const void* w_vals,

@@ -23,8 +23,9 @@
 // published and the ring slot of the finished unit is handed back to the loaders.
 //
 // Epilogue.  D[channel][token] leaves each lane with 64 consecutive output channels of one token; the
-// scaled bf16 values are staged through the (then idle) LDS so that every global store instruction
-// writes whole 256-byte row segments.
+// scaled bf16 values are staged through LDS so that every global store instruction writes whole
+// 256-byte row segments.  Staging takes 64 KB placed over ring slots the next tile's first unit does
+// not use: that unit is requested before the epilogue and lands while the results are written out.
 #include "ss_common.h"
 #include "packed_layout.h"
 #include <type_traits>
@@ -42,14 +43,29 @@ constexpr int ROWB = 128; // bytes of one LDS row of a row-major operand tile (o
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void gbl_void;
 
-// 16 (or 4) bytes per lane, global -> LDS; the LDS address is wave-uniform base + lane * size
-__device__ inline void lds_dma16(const void* g, void* lds_wave_base)
+// 16 (or 4) bytes per lane, global -> LDS; the LDS address is wave-uniform base + lane * size.  The global
+// address is given as a wave-uniform pointer plus a 32-bit lane offset; the empty asm pins the uniform part
+// in scalar registers so that the load uses its scalar-base addressing form and the lane part stays one
+// 32-bit register (otherwise the compiler keeps a 64-bit per-lane address alive for every load stream).
+__device__ inline void lds_dma16(const uint8_t* uniform_base, uint32_t lane_off, void* lds_wave_base)
 {
-    __builtin_amdgcn_global_load_lds((gbl_void*)g, (lds_void*)lds_wave_base, 16, 0, 0);
+    asm volatile("" : "+s"(uniform_base));
+    __builtin_amdgcn_global_load_lds((gbl_void*)(uniform_base + lane_off), (lds_void*)lds_wave_base, 16, 0, 0);
 }
-__device__ inline void lds_dma4(const void* g, void* lds_wave_base)
+__device__ inline void lds_dma4(const uint8_t* uniform_base, uint32_t lane_off, void* lds_wave_base)
 {
-    __builtin_amdgcn_global_load_lds((gbl_void*)g, (lds_void*)lds_wave_base, 4, 0, 0);
+    asm volatile("" : "+s"(uniform_base));
+    __builtin_amdgcn_global_load_lds((gbl_void*)(uniform_base + lane_off), (lds_void*)lds_wave_base, 4, 0, 0);
+}
+
+// Lane id read from the hardware.  Code that runs once per tile (loader set-up, epilogue) takes the lane id from
+// here instead of keeping threadIdx-derived values alive through the k loop, where every register is taken:
+// what the compiler cannot keep it spills, and a spill reload waits for all direct loads in flight.
+__device__ inline int fresh_lane()
+{
+    int l;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
+    return l;
 }
 
 // Wait until at most N of this wave's direct loads are still in flight and all of its LDS reads
@@ -108,21 +124,23 @@ constexpr int ROW_LOADS = 256 / (8 * G_WAVES);      // 8 rows per wavefront-wide
 struct RowTileLoader {
     const uint8_t* base;                            // first row of the tile (wave-uniform, lives in SGPRs)
     uint32_t off[ROW_LOADS];                        // this lane's byte offset from it, per load
-    __device__ void init(const uint8_t* mat, int64_t ld, int64_t row0, int64_t nrows, int wave, int lane)
+    __device__ void init(const uint8_t* mat, int64_t ld, int64_t row0, int64_t nrows, int wave)
     {
+        const int lane = fresh_lane();
         base = mat + row0 * ld;
+        const int64_t left = nrows - row0;             // rows of the matrix from row0 on (>= 1)
+        const int last = left > 255 ? 255 : (int)left - 1;
+        const uint32_t ld32 = (uint32_t)ld;             // 256 rows x ld fits 32 bits (row bytes <= 2^23)
 #pragma unroll
         for (int i = 0; i < ROW_LOADS; ++i) {
             const int row = (i * G_WAVES + wave) * 8 + (lane >> 3);
             const int lc = (lane & 7) ^ swz(row);
-            int64_t grow = row0 + row;
-            grow = grow < nrows ? grow : nrows - 1;
-            off[i] = (uint32_t)((grow - row0) * ld) + lc * 16;
+            off[i] = (uint32_t)(row < last ? row : last) * ld32 + lc * 16;
         }
     }
     __device__ void issue_one(int i, int64_t k0, uint8_t* lds_tile, int wave) const
     {
-        lds_dma16(base + k0 + off[i], lds_tile + (i * G_WAVES + wave) * 8 * ROWB);
+        lds_dma16(base + k0, off[i], lds_tile + (i * G_WAVES + wave) * 8 * ROWB);
     }
     __device__ void issue(int64_t k0, uint8_t* lds_tile, int wave) const
     {
@@ -146,41 +164,46 @@ __device__ inline uint32_t pack_bf16x2(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-constexpr int EP_ROWB = 272;                        // 128 channels x 2 B + 16 B pad (bank spread)
-constexpr int EP_TILE_BYTES = 256 * 2 * EP_ROWB;    // 256 tokens x 2 channel panels
+// Staging holds half a wavefront sub-tile at a time: 32 tokens x 128 channels of bf16 = 32 rows of 256
+// bytes per wavefront, 64 KB per workgroup.  No row padding: the 16-byte chunk c of row r is stored at
+// chunk c ^ (r & 15), which spreads both the column-wise writes and the row-wise reads over all banks.
+constexpr int EP_ROWB = 256;
+constexpr int EP_WAVE_BYTES = 32 * EP_ROWB;         // 8 KB
+constexpr int EP_BYTES = G_WAVES * EP_WAVE_BYTES;   // 64 KB
 
-// acc[f][b][r] of lane (n = lane & 31, h = lane >> 5) is channel o_base + 64 h + 16 f + r of token
-// t_base + 32 b + n.  `stage` is this wavefront's private 32 NBF rows of EP_ROWB bytes of LDS.
-// SCALED = false (bf16 operands): Y = bf16(acc), s_x and s_w are not touched.
+// acc[f][b][r] of lane (n = lane & 31, h = lane >> 5) is channel 64 h + 16 f + r, token 32 b + n of this
+// wavefront's 128-channel x 64-token sub-tile, whose first element is Y_sub (wave-uniform) and of which
+// rows_left tokens x cols_left channels exist.  `stage` is this wavefront's private EP_WAVE_BYTES of LDS;
+// `sw_lds` holds the sub-tile's 128 channel scales in LDS (fetched with the tile's first unit), s_x_sub
+// points at its first token scale.  All lane-dependent offsets are 32-bit (ldy < 2^22).
+// SCALED = false (bf16 operands): Y = bf16(acc), the scales are not touched.
 template <bool SCALED, typename ACC>
-__device__ inline void store_tile(const ACC (&acc)[4][NBF], const float* __restrict__ s_x, const float* __restrict__ s_w, uint16_t* __restrict__ Y,
-                                  int64_t ldy, int64_t M, int64_t O, int64_t o_base, int64_t t_base, uint8_t* stage)
+__device__ inline void store_tile(const ACC (&acc)[4][NBF], const float* __restrict__ s_x_sub, const float* sw_lds, uint16_t* __restrict__ Y_sub,
+                                  uint32_t ldy, int rows_left, int cols_left, uint8_t* stage)
 {
-    const int lane = threadIdx.x & 63, n = lane & 31, h = lane >> 5;
-    const int64_t o0 = o_base + 64 * h;
-    const bool sw_vec = (o0 + 64 <= O) && (((uintptr_t)s_w & 15) == 0);
+    const int lane = fresh_lane(), n = lane & 31, h = lane >> 5;
+    const bool vec_ok = ((ldy & 7) == 0) && (((uintptr_t)Y_sub & 15) == 0);
+    const int seg = lane & 15;                      // 16-byte segment (8 channels) of the 256-byte row
+    const int oc = 8 * seg;
+    const uint32_t lane_elem = (uint32_t)(lane >> 4) * ldy + (uint32_t)oc;   // this lane's element offset in its first row
 #pragma unroll
-    for (int f = 0; f < 4; ++f) {
-        float sw[16];
-        if constexpr (!SCALED) {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) sw[i] = 1.0f;
-        } else if (sw_vec) {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float4 v = reinterpret_cast<const float4*>(s_w + o0 + 16 * f)[i];
-                sw[4 * i] = v.x; sw[4 * i + 1] = v.y; sw[4 * i + 2] = v.z; sw[4 * i + 3] = v.w;
-            }
-        } else {
-#pragma unroll
-            for (int i = 0; i < 16; ++i) { const int64_t o = o0 + 16 * f + i; sw[i] = s_w[o < O ? o : O - 1]; }
+    for (int b = 0; b < NBF; ++b) {
+        float sx = 1.0f;
+        if constexpr (SCALED) {
+            uint32_t tk = (uint32_t)(b * 32 + n);
+            tk = (int)tk < rows_left ? tk : (uint32_t)(rows_left - 1);
+            sx = rows_left > 0 ? s_x_sub[tk] : 1.0f;
         }
 #pragma unroll
-        for (int b = 0; b < NBF; ++b) {
-            const int64_t tok = t_base + b * 32 + n;
+        for (int f = 0; f < 4; ++f) {
             uint32_t w[8];
             if constexpr (SCALED) {
-                const float sx = s_x[tok < M ? tok : M - 1];
+                float sw[16];
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float4 v = reinterpret_cast<const float4*>(sw_lds + 64 * h + 16 * f)[i];
+                    sw[4 * i] = v.x; sw[4 * i + 1] = v.y; sw[4 * i + 2] = v.z; sw[4 * i + 3] = v.w;
+                }
 #pragma unroll
                 for (int q = 0; q < 8; ++q)
                     w[q] = pack_bf16x2(((float)acc[f][b][2 * q] * sx) * sw[2 * q], ((float)acc[f][b][2 * q + 1] * sx) * sw[2 * q + 1]);
@@ -188,34 +211,34 @@ __device__ inline void store_tile(const ACC (&acc)[4][NBF], const float* __restr
 #pragma unroll
                 for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2((float)acc[f][b][2 * q], (float)acc[f][b][2 * q + 1]);
             }
-            uint4* dst = reinterpret_cast<uint4*>(stage + (b * 32 + n) * EP_ROWB + h * 128 + 32 * f);
-            dst[0] = make_uint4(w[0], w[1], w[2], w[3]);
-            dst[1] = make_uint4(w[4], w[5], w[6], w[7]);
+            const int c = h * 8 + 2 * f;            // first of the two 16-byte chunks of this lane's 16 channels
+            uint8_t* row = stage + n * EP_ROWB;
+            *reinterpret_cast<uint4*>(row + (((c) ^ (n & 15)) << 4)) = make_uint4(w[0], w[1], w[2], w[3]);
+            *reinterpret_cast<uint4*>(row + (((c + 1) ^ (n & 15)) << 4)) = make_uint4(w[4], w[5], w[6], w[7]);
         }
-    }
-    // wavefront-private staging: its own LDS writes only need to have completed
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    const bool vec_ok = ((ldy & 7) == 0) && (((uintptr_t)Y & 15) == 0) && ((o_base & 7) == 0);
-    const int seg = lane & 15;                      // 16-byte segment (8 channels) of the 256-byte row
-    const int64_t o = o_base + 8 * seg;
-#pragma unroll 8
-    for (int i = 0; i < 8 * NBF; ++i) {
-        const int r = 4 * i + (lane >> 4);
-        const int64_t tok = t_base + r;
-        const uint4 v = *reinterpret_cast<const uint4*>(stage + r * EP_ROWB + seg * 16);
-        if (tok < M) {
-            uint16_t* dst = Y + tok * ldy + o;
-            if (vec_ok && o + 8 <= O) {
-                // Y is written once and not read again by this kernel: stream it past the caches
-                typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-                __builtin_nontemporal_store((u32x4){v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(dst));
-            } else {
-                const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+        // wavefront-private staging: its own LDS writes only need to have completed
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
 #pragma unroll
-                for (int e = 0; e < 8; ++e)
-                    if (o + e < O) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+        for (int i = 0; i < 8; ++i) {
+            const int r = 4 * i + (lane >> 4);
+            const int tk = b * 32 + r;
+            const uint4 v = *reinterpret_cast<const uint4*>(stage + r * EP_ROWB + ((seg ^ (r & 15)) << 4));
+            if (tk < rows_left) {
+                uint16_t* dst = Y_sub + (lane_elem + (uint32_t)(b * 32 + 4 * i) * ldy);
+                if (vec_ok && oc + 8 <= cols_left) {
+                    // Y is written once and not read again by this kernel: stream it past the caches
+                    typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+                    __builtin_nontemporal_store((u32x4){v.x, v.y, v.z, v.w}, reinterpret_cast<u32x4*>(dst));
+                } else {
+                    const uint32_t wv[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+                    for (int e = 0; e < 8; ++e)
+                        if (oc + e < cols_left) dst[e] = (uint16_t)(wv[e >> 1] >> (16 * (e & 1)));
+                }
             }
         }
+        // the reads of this half have returned (their data went out with the stores) before the next half is staged
+        asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
     }
 }
 
@@ -280,7 +303,9 @@ constexpr std::integral_constant<int, 1> odd{};
 // ---- dense: Y = Xq . Wq^T ----------------------------------------------------------------------------
 // Units of 128 k-bytes (128 / DENSE_SUB sub-steps); rings of two units per operand.  Kb = bytes per row.
 constexpr int D_UNIT = BO * ROWB;                   // 32 KB, same for A and B
-constexpr int D_LDS = EP_TILE_BYTES > 4 * D_UNIT ? EP_TILE_BYTES : 4 * D_UNIT;   // rings 128 KB; staging 136 KB
+constexpr int SW_BYTES = BO * 4;                     // the tile's 256 channel scales; two copies (this tile, next tile)
+constexpr int D_SW_OFF = 4 * D_UNIT;
+constexpr int D_LDS = D_SW_OFF + 2 * SW_BYTES;      // 130 KB
 
 template <int DT>
 __global__ __launch_bounds__(G_THREADS) void k_dense(const uint8_t* __restrict__ Xq, const float* __restrict__ s_x, const uint8_t* __restrict__ Wq,
@@ -303,21 +328,43 @@ __global__ __launch_bounds__(G_THREADS) void k_dense(const uint8_t* __restrict__
 #pragma unroll
     for (int bb = 0; bb < NBF; ++bb) brow[bb] = wt * (32 * NBF) + bb * 32 + row;
 
-    int to, tt;
-    for (int round = 0; tile_of_round(round, tiles_o, tiles_t, to, tt); ++round) {
-        const int64_t o_blk = (int64_t)to * BO, t_blk = (int64_t)tt * BT;
-        RowTileLoader la, lb;
-        la.init(Wq, Kb, o_blk, O, wave, lane);
-        lb.init(Xq, Kb, t_blk, M, wave, lane);
-        // direct load number j (0..7) of this wavefront for a unit: weight and token rows alternate
-        auto issue_part = [&](int unit, int j) {
-            if (j & 1) lb.issue_one(j >> 1, (int64_t)unit * ROWB, smem + 2 * D_UNIT + (unit & 1) * D_UNIT, wave);
-            else la.issue_one(j >> 1, (int64_t)unit * ROWB, smem + (unit & 1) * D_UNIT, wave);
-        };
-        auto issue = [&](int unit) {
+    // Per-tile state of the loaders.  It is set up for the next tile before the current tile's epilogue, so that
+    // the first unit of the next tile is already in flight while the results are written out.
+    RowTileLoader la, lb;
+    int64_t o_blk = 0, t_blk = 0;
+    auto setup_tile = [&](int to, int tt) {
+        o_blk = (int64_t)to * BO;
+        t_blk = (int64_t)tt * BT;
+        la.init(Wq, Kb, o_blk, O, wave);
+        lb.init(Xq, Kb, t_blk, M, wave);
+    };
+    // direct load number j (0..7) of this wavefront for a unit: weight and token rows alternate
+    auto issue_part = [&](int unit, int j) {
+        if (j & 1) lb.issue_one(j >> 1, (int64_t)unit * ROWB, smem + 2 * D_UNIT + (unit & 1) * D_UNIT, wave);
+        else la.issue_one(j >> 1, (int64_t)unit * ROWB, smem + (unit & 1) * D_UNIT, wave);
+    };
+    auto issue = [&](int unit) {
 #pragma unroll
-            for (int j = 0; j < 2 * ROW_LOADS; ++j) issue_part(unit, j);
-        };
+        for (int j = 0; j < 2 * ROW_LOADS; ++j) issue_part(unit, j);
+    };
+    // one more direct load per wavefront with unit 0 of a tile: its channel scales (4 bytes a lane; waves 4..7
+    // repeat what waves 0..3 fetch, so that every wavefront has the same number of loads in flight)
+    auto issue_scales = [&](int parity) {
+        if constexpr (MM::SCALED) {
+            const int64_t o_first = o_blk + (wave & 3) * 64, left = O - 1 - o_first;     // clamp to the last channel
+            const int left32 = left > 63 ? 63 : (int)left, ln = fresh_lane();
+            const uint32_t oc = left32 < 0 ? 0u : (uint32_t)(ln < left32 ? ln : left32);
+            lds_dma4(reinterpret_cast<const uint8_t*>(s_w + (left < 0 ? O - 1 : o_first)), oc * 4, smem + D_SW_OFF + parity * SW_BYTES + (wave & 3) * 256);
+        }
+    };
+        // The epilogue stages in the second ring slot of either operand (waves 0..3 in A's, 4..7 in B's), so the first
+    // slots can take unit 0 of the next tile while the epilogue runs.
+    uint8_t* const stage = smem + (wave < 4 ? D_UNIT : 3 * D_UNIT) + (wave & 3) * EP_WAVE_BYTES;
+
+    int to, tt;
+    bool have = tile_of_round(0, tiles_o, tiles_t, to, tt);
+    if (have) { setup_tile(to, tt); issue(0); issue_scales(0); }
+    for (int round = 0; have; ++round) {
         typename MM::acc_t acc[4][NBF];
         zero_acc(acc);
         Frags R;
@@ -372,10 +419,10 @@ __global__ __launch_bounds__(G_THREADS) void k_dense(const uint8_t* __restrict__
         // the last sub-step of unit u (half of the loads ride on that sub-step, half on the next one), and
         // is awaited before the last sub-step of unit u+1.
         if (round > 0) wg_barrier();                  // epilogue staging of the previous tile has been read out
-        issue(0);
         if (nunits > 1) issue(1);
+        // unit 0 was requested before the previous epilogue, whose stores sit between it and unit 1
         if (nunits > 1) wait_vmcnt<2 * ROW_LOADS>(); else wait_vmcnt<0>();
-        wg_barrier();                                 // unit 0 is published
+        wg_barrier();                                 // unit 0 (and the channel scales) are published
 #pragma unroll
         for (int part = 0; part < NPARTS; ++part) read_part(0, part, 0);
         wait_lgkm0();
@@ -399,7 +446,18 @@ __global__ __launch_bounds__(G_THREADS) void k_dense(const uint8_t* __restrict__
         wait_lgkm0();
         sub_step(t + NSUB - 1, odd, std::false_type{}, no_loads, 0);
         wg_barrier();                                 // every wave is done with the operand tiles: LDS becomes staging
-        store_tile<MM::SCALED>(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
+        const int64_t o_cur = o_blk, t_cur = t_blk;
+        have = tile_of_round(round + 1, tiles_o, tiles_t, to, tt);
+        if (have) { setup_tile(to, tt); issue(0); issue_scales((round + 1) & 1); }
+        {
+            const int64_t o_sub = o_cur + wo * 128, t_sub = t_cur + wt * (32 * NBF);
+            const int64_t rows = M - t_sub, cols = O - o_sub;      // <= 0: nothing of this sub-tile exists
+            const bool any = rows > 0 && cols > 0;
+            store_tile<MM::SCALED>(acc, MM::SCALED && any ? s_x + t_sub : s_x,
+                                   reinterpret_cast<const float*>(smem + D_SW_OFF + (round & 1) * SW_BYTES) + wo * 128,
+                                   any ? Y + t_sub * ldy + o_sub : Y, (uint32_t)ldy,
+                                   any ? (int)(rows > 64 ? 64 : rows) : 0, any ? (int)(cols > 128 ? 128 : cols) : 0, stage);
+        }
     }
 }
 
@@ -415,8 +473,9 @@ constexpr int S_AV_UNIT = BO * 64;                  // 16 KB
 constexpr int S_AM_UNIT = BO * 16;                  // 4 KB
 constexpr int S_AV_OFF = S_RING * S_B_UNIT;
 constexpr int S_AM_OFF = S_AV_OFF + S_RING * S_AV_UNIT;
-constexpr int S_LDS = S_AM_OFF + S_RING * S_AM_UNIT;  // 159744 bytes
-static_assert(S_LDS <= 160 * 1024 && EP_TILE_BYTES <= S_LDS && EP_TILE_BYTES <= D_LDS, "LDS budget");
+constexpr int S_SW_OFF = S_AM_OFF + S_RING * S_AM_UNIT;
+constexpr int S_LDS = S_SW_OFF + 2 * SW_BYTES;      // 158 KB
+static_assert(S_LDS <= 160 * 1024 && EP_BYTES <= 2 * S_B_UNIT && EP_WAVE_BYTES * 4 <= D_UNIT, "LDS budget");
 constexpr int S_LPU = ROW_LOADS + 2 + 2;            // direct loads per wavefront and unit: token rows, values, index words
 
 // weight values single-buffered; index words and token fragments double-buffered by sub-step parity
@@ -438,35 +497,57 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse(const uint8_t* __restrict_
 #pragma unroll
     for (int bb = 0; bb < NBF; ++bb) brow[bb] = wt * (32 * NBF) + bb * 32 + n;
 
-    int to, tt;
-    for (int round = 0; tile_of_round(round, tiles_o, tiles_t, to, tt); ++round) {
-        const int64_t o_blk = (int64_t)to * BO, t_blk = (int64_t)tt * BT;
-        RowTileLoader lb;
-        lb.init(XL, Kpb, t_blk, M, wave, lane);
-        // Packed weights: per 128-channel panel the two sub-steps of a unit are contiguous, 8 KB of values
-        // and 2 KB of index words.  Waves 0..3 fetch panel 2*to, waves 4..7 panel 2*to+1 (clamped to the last
-        // panel; a clamped panel only feeds rows that are never stored): two 1 KB pieces of values (16 bytes
-        // a lane) and two 256-byte pieces of index words (4 bytes a lane) each.
+    // Per-tile state of the loaders.  It is set up for the next tile before the current tile's epilogue, so that
+    // the first unit of the next tile is already in flight while the results are written out.
+    RowTileLoader lb;
+    const uint8_t *av_src = nullptr, *am_src = nullptr;
+    int64_t o_blk = 0, t_blk = 0;
+    const int piece = (wave & 3) * 2;
+    uint8_t* const av_dst = smem + S_AV_OFF + (wave >> 2) * 8192 + piece * 1024;
+    uint8_t* const am_dst = smem + S_AM_OFF + (wave >> 2) * 2048 + piece * 256;
+    const uint32_t lane16 = lane * 16, lane4 = lane * 4;
+    // Packed weights: per 128-channel panel the two sub-steps of a unit are contiguous, 8 KB of values
+    // and 2 KB of index words.  Waves 0..3 fetch panel 2*to, waves 4..7 panel 2*to+1 (clamped to the last
+    // panel; a clamped panel only feeds rows that are never stored): two 1 KB pieces of values (16 bytes
+    // a lane) and two 256-byte pieces of index words (4 bytes a lane) each.
+    auto setup_tile = [&](int to, int tt) {
+        o_blk = (int64_t)to * BO;
+        t_blk = (int64_t)tt * BT;
+        lb.init(XL, Kpb, t_blk, M, wave);
         int64_t panel = (int64_t)to * 2 + (wave >> 2);
         panel = panel < npanels ? panel : npanels - 1;
-        const int piece = (wave & 3) * 2;
-        const uint8_t* av_src = w_vals + panel * U * 8192 + piece * 1024;     // wave-uniform
-        const uint8_t* am_src = w_meta + panel * U * 2048 + piece * 256;
-        uint8_t* av_dst = smem + S_AV_OFF + (wave >> 2) * 8192 + piece * 1024;
-        uint8_t* am_dst = smem + S_AM_OFF + (wave >> 2) * 2048 + piece * 256;
-        const uint32_t lane16 = lane * 16, lane4 = lane * 4;
-        // direct load number j (0..7) of this wavefront for unit u: token rows, values, token rows, index words, twice
-        auto issue_part = [&](int u, int slot, int j) {
-            const int half = j >> 2;
-            if (!(j & 1)) lb.issue_one(j >> 1, (int64_t)u * ROWB, smem + slot * S_B_UNIT, wave);
-            else if ((j & 3) == 1) lds_dma16(av_src + (int64_t)u * 8192 + half * 1024 + lane16, av_dst + slot * S_AV_UNIT + half * 1024);
-            else lds_dma4(am_src + (int64_t)u * 2048 + half * 256 + lane4, am_dst + slot * S_AM_UNIT + half * 256);
-        };
-        auto issue = [&](int u, int slot) {
+        av_src = w_vals + panel * U * 8192 + piece * 1024;     // wave-uniform
+        am_src = w_meta + panel * U * 2048 + piece * 256;
+    };
+    // direct load number j (0..7) of this wavefront for unit u: token rows, values, token rows, index words, twice
+    auto issue_part = [&](int u, int slot, int j) {
+        const int half = j >> 2;
+        if (!(j & 1)) lb.issue_one(j >> 1, (int64_t)u * ROWB, smem + slot * S_B_UNIT, wave);
+        else if ((j & 3) == 1) lds_dma16(av_src + (int64_t)u * 8192 + half * 1024, lane16, av_dst + slot * S_AV_UNIT + half * 1024);
+        else lds_dma4(am_src + (int64_t)u * 2048 + half * 256, lane4, am_dst + slot * S_AM_UNIT + half * 256);
+    };
+    auto issue = [&](int u, int slot) {
 #pragma unroll
-            for (int j = 0; j < S_LPU; ++j) issue_part(u, slot, j);
-        };
+        for (int j = 0; j < S_LPU; ++j) issue_part(u, slot, j);
+    };
+    // one more direct load per wavefront with unit 0 of a tile: its channel scales (4 bytes a lane; waves 4..7
+    // repeat what waves 0..3 fetch, so that every wavefront has the same number of loads in flight)
+    auto issue_scales = [&](int parity) {
+        if constexpr (MM::SCALED) {
+            const int64_t o_first = o_blk + (wave & 3) * 64, left = O - 1 - o_first;     // clamp to the last channel
+            const int left32 = left > 63 ? 63 : (int)left, ln = fresh_lane();
+            const uint32_t oc = left32 < 0 ? 0u : (uint32_t)(ln < left32 ? ln : left32);
+            lds_dma4(reinterpret_cast<const uint8_t*>(s_w + (left < 0 ? O - 1 : o_first)), oc * 4, smem + S_SW_OFF + parity * SW_BYTES + (wave & 3) * 256);
+        }
+    };
 
+    // Unit u of a tile lives in ring slot (u + 2) % 3: the epilogue's staging area is the token part of
+    // slots 0 and 1, so slot 2 (and the weight parts of all slots) can take the next tile's first unit
+    // while the epilogue runs.
+    int to, tt;
+    bool have = tile_of_round(0, tiles_o, tiles_t, to, tt);
+    if (have) { setup_tile(to, tt); issue(0, 2); issue_scales(0); }
+    for (int round = 0; have; ++round) {
         typename MM::acc_t acc[4][NBF];
         zero_acc(acc);
         SparseFrags R;
@@ -510,16 +591,16 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse(const uint8_t* __restrict_
         // has seen its own loads of the next unit land; after it nobody reads the unit's ring slot any more,
         // so the unit three ahead is requested into it, and the next unit is visible to everybody.
         if (round > 0) wg_barrier();                  // epilogue staging of the previous tile has been read out
-        issue(0, 0);
-        if (U > 1) issue(1, 1);
-        if (U > 2) issue(2, 2);
+        if (U > 1) issue(1, 0);
+        if (U > 2) issue(2, 1);
+        // unit 0 was requested before the previous epilogue, whose stores sit between it and units 1 and 2
         if (U > 2) wait_vmcnt<2 * S_LPU>(); else if (U > 1) wait_vmcnt<S_LPU>(); else wait_vmcnt<0>();
-        wg_barrier();                                 // unit 0 is published
+        wg_barrier();                                 // unit 0 (and the channel scales) are published
 #pragma unroll
-        for (int part = 0; part < 9; ++part) read_part(0, 0, part);
+        for (int part = 0; part < 9; ++part) read_part(2, 0, part);
         wait_lgkm0();
         constexpr std::true_type prefetch{};
-        int u = 0, slot = 0;
+        int u = 0, slot = 2;
         sub_step(slot, 1, prefetch, no_loads, 0, 0);
         for (; u + 3 < U; ++u) {                      // units u+1 and u+2 are in flight, unit u+3 gets requested
             const int nslot = slot == S_RING - 1 ? 0 : slot + 1;
@@ -542,7 +623,18 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse(const uint8_t* __restrict_
         wait_lgkm0();
         sub_step(slot, 0, std::false_type{}, no_loads, 0, 0);
         wg_barrier();                                 // every wave is done with the operand tiles: LDS becomes staging
-        store_tile<MM::SCALED>(acc, s_x, s_w, Y, ldy, M, O, o_blk + wo * 128, t_blk + wt * (32 * NBF), smem + wave * (32 * NBF * EP_ROWB));
+        const int64_t o_cur = o_blk, t_cur = t_blk;
+        have = tile_of_round(round + 1, tiles_o, tiles_t, to, tt);
+        if (have) { setup_tile(to, tt); issue(0, 2); issue_scales((round + 1) & 1); }
+        {
+            const int64_t o_sub = o_cur + wo * 128, t_sub = t_cur + wt * (32 * NBF);
+            const int64_t rows = M - t_sub, cols = O - o_sub;      // <= 0: nothing of this sub-tile exists
+            const bool any = rows > 0 && cols > 0;
+            store_tile<MM::SCALED>(acc, MM::SCALED && any ? s_x + t_sub : s_x,
+                                   reinterpret_cast<const float*>(smem + S_SW_OFF + (round & 1) * SW_BYTES) + wo * 128,
+                                   any ? Y + t_sub * ldy + o_sub : Y, (uint32_t)ldy,
+                                   any ? (int)(rows > 64 ? 64 : rows) : 0, any ? (int)(cols > 128 ? 128 : cols) : 0, smem + wave * EP_WAVE_BYTES);
+        }
     }
 }
 
@@ -563,7 +655,7 @@ static ss_status check_gemm(const void* X, const float* s_x, const void* W, cons
                             ss_dtype dtype, const void* Y, int64_t ldy)
 {
     if (dtype != SS_I8 && dtype != SS_FP8_E4M3 && dtype != SS_BF16) return SS_ERR_DTYPE;
-    if (M < 0 || O < 0 || K <= 0 || (K * elem_size(dtype)) % KSTEP != 0 || ldy < O || M > (1 << 24) || O > (1 << 24) || K > (1 << 24))
+    if (M < 0 || O < 0 || K <= 0 || (K * elem_size(dtype)) % KSTEP != 0 || ldy < O || M > (1 << 24) || ldy >= (1 << 22) || K * elem_size(dtype) > (1 << 23))
         return SS_ERR_SHAPE;
     if (M == 0 || O == 0) return SS_OK;
     if (!X || !W || !Y) return SS_ERR_NULL;
