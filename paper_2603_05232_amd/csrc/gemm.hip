@@ -28,6 +28,7 @@
 // not use: that unit is requested before the epilogue and lands while the results are written out.
 #include "ss_common.h"
 #include "packed_layout.h"
+#include "mma_types.h"
 #include <type_traits>
 
 
@@ -155,14 +156,6 @@ __device__ inline const v4i* tile_chunk(const uint8_t* lds_tile, int row, int lc
 }
 
 // ---- epilogue: Y = bf16((float(acc) * s_x) * s_w), staged through LDS for coalesced stores ------
-// two fp32 -> packed bf16 (round to nearest even) in one v_cvt_pk_bf16_f32
-__device__ inline uint32_t pack_bf16x2(float a, float b)
-{
-    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-    typedef float f32x2 __attribute__((ext_vector_type(2)));
-    const f32x2 v = {a, b};
-    return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
-}
 
 // Staging holds half a wavefront sub-tile at a time: 32 tokens x 128 channels of bf16 = 32 rows of 256
 // bytes per wavefront, 64 KB per workgroup.  No row padding: the 16-byte chunk c of row r is stored at
@@ -251,45 +244,6 @@ template <typename ACC> __device__ inline void zero_acc(ACC (&acc)[4][NBF])
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[f][b][r] = 0;
 }
-
-// ---- matrix instructions per operand type -----------------------------------------------------------
-// Sparse: one instruction is 32 channels x 32 tokens x 64 lifted bytes (A = 16 bytes of stored values + an
-// index word per lane, B = 32 bytes per lane).  Dense: DENSE_SUB k-bytes per instruction, A and B
-// DENSE_SUB / 2 bytes per lane; lane (row, q) holds the bytes [q DENSE_SUB / 2, (q + 1) DENSE_SUB / 2) of
-// its row within the instruction's k range, for both operands (measured: element e of A lane (i, q)
-// meets element e of B lane (n, q)).
-template <int DT> struct Mma;
-template <> struct Mma<SS_I8> {
-    typedef v16i acc_t;
-    typedef v4i dfrag_t;
-    static constexpr int DENSE_SUB = 32;
-    static constexpr bool SCALED = true;
-    __device__ static acc_t sparse(v4i a, v8i b, acc_t c, int idx) { return __builtin_amdgcn_smfmac_i32_32x32x64_i8(a, b, c, idx, 0, 0); }
-    __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
-};
-template <> struct Mma<SS_FP8_E4M3> {
-    typedef v16f acc_t;
-    typedef v8i dfrag_t;
-    static constexpr int DENSE_SUB = 64;
-    static constexpr bool SCALED = true;
-    __device__ static acc_t sparse(v4i a, v8i b, acc_t c, int idx) { return __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(a, b, c, idx, 0, 0); }
-    // format selectors 0 = e4m3 for both operands; block scales 0 = the unscaled form of the instruction
-    __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c) { return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0); }
-};
-template <> struct Mma<SS_BF16> {
-    typedef v16f acc_t;
-    typedef v4i dfrag_t;
-    static constexpr int DENSE_SUB = 32;
-    static constexpr bool SCALED = false;
-    __device__ static acc_t sparse(v4i a, v8i b, acc_t c, int idx)
-    {
-        return __builtin_amdgcn_smfmac_f32_32x32x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v16bf, b), c, idx, 0, 0);
-    }
-    __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c)
-    {
-        return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
-    }
-};
 
 // operand reads [first, last) that go behind matrix instruction i of 8 when `parts` reads are spread evenly
 __device__ constexpr int part_begin(int i, int parts) { return (i * parts + 7) / 8; }
@@ -690,6 +644,8 @@ extern "C" ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq
 {
     ss_status st = check_gemm(Xq, s_x, Wq, s_w, M, O, K, dtype, Y, ldy);
     if (st != SS_OK || M == 0 || O == 0) return st;
+    if (use_skinny(M, O))
+        return launch_dense_skinny(Xq, s_x, Wq, s_w, M, O, K * elem_size(dtype), dtype, Y, ldy, static_cast<hipStream_t>(stream));
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
     const int grid = persistent_grid(tiles_o * tiles_t);
     if (grid <= 0) return SS_ERR_HIP;
@@ -710,6 +666,9 @@ extern "C" ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, c
     if (st != SS_OK || M == 0 || O == 0) return st;
     if (!w_meta) return SS_ERR_NULL;
     if ((uintptr_t)w_meta & 15) return SS_ERR_SHAPE;
+    if (use_skinny(M, O))
+        return launch_sparse_skinny(X_lifted, s_x, w_vals, w_meta, s_w, M, O, K_lifted * elem_size(dtype), dtype, Y, ldy,
+                                    static_cast<hipStream_t>(stream));
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
     const int grid = persistent_grid(tiles_o * tiles_t);
     if (grid <= 0) return SS_ERR_HIP;
