@@ -256,3 +256,24 @@ def test_sparse_and_dense_gemm_float(dtype, N, M, O, K):
     assert np.array_equal(bits16(Ys), exp)
     Yd = binding.dense_gemm(to_dev_q(Xq_i, dtype), sxd, Wq_t, swd, dtype)
     assert np.array_equal(bits16(Yd), exp)
+
+
+# ------------------------------------------------------------------ kernel selection boundaries
+@pytest.mark.parametrize("M,O", [(32, 128), (33, 160), (64, 8192), (65, 8192), (65, 16384 + 256), (128, 512), (129, 512), (128, 16384)])
+def test_gemm_kernel_selection_boundaries_int8(M, O):
+    """Token counts around the switch between the few-token kernels (M <= 64, or M <= 128 with few channel
+    tiles) and the 256 x 256 tile kernels: the result must not depend on which one runs."""
+    N, K = 4, 256
+    rng = np.random.default_rng(M * 7 + O)
+    Wq = rng.integers(-127, 128, size=(O, K)).astype(np.int8)
+    keep = np.argsort(rng.random((O, K // 8, 8)), axis=-1) < 6
+    Wq = (Wq.reshape(O, K // 8, 8) * keep).reshape(O, K).astype(np.int8)
+    Xq = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    s_x = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    s_w = rng.uniform(1e-4, 1e-3, O).astype(np.float32)
+    exp = so.epilogue(_acc_big(Xq, Wq), s_x, s_w, "i8")
+    w_vals, w_meta = binding.slide_decompose(dev(Wq), N, "i8")
+    Ys = binding.slide_sparse_gemm(dev(so.lift(Xq, N)), dev(s_x), w_vals, w_meta, dev(s_w), O, "i8")
+    assert np.array_equal(bits16(Ys), exp)
+    Yd = binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8")
+    assert np.array_equal(bits16(Yd), exp)
