@@ -112,13 +112,16 @@ ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_
  * dense row-major from act_lift_quant; w_vals/w_meta from slide_decompose for the same
  * O and K_lifted.  Y is bf16 [M,O] with row stride ldy (elements, O <= ldy < 2^22).  INT8 accumulates
  * in int32 (exact), FP8 and BF16 in fp32 in the order of the matrix instructions.
- * Requires K_lifted * sizeof(element) % 128 == 0 and 16-byte aligned operand pointers. */
+ * Requires K_lifted * sizeof(element) % 128 == 0 (and <= 2^23 bytes per row), M <= 2^24, and 16-byte
+ * aligned operand pointers.  For M <= 64 (or M <= 128 with O < 16384) kernels that stream the weights once
+ * are used instead of the 256 x 256 tile kernels; results are the same (INT8) or within rounding order. */
 ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, const void* w_vals,
                             const void* w_meta, const float* s_w, int64_t M, int64_t O,
                             int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy, void* stream);
 
 /* Dense baseline at the original K with the same epilogue: Xq[M,K], Wq[O,K] row-major.
- * Requires K * sizeof(element) % 128 == 0 and 16-byte aligned operand pointers. */
+ * Requires K * sizeof(element) % 128 == 0 (and <= 2^23 bytes per row), M <= 2^24, O <= ldy < 2^22, and
+ * 16-byte aligned operand pointers. */
 ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq, const float* s_w,
                      int64_t M, int64_t O, int64_t K, ss_dtype dtype, void* Y, int64_t ldy,
                      void* stream);

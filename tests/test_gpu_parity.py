@@ -277,3 +277,54 @@ def test_gemm_kernel_selection_boundaries_int8(M, O):
     assert np.array_equal(bits16(Ys), exp)
     Yd = binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8")
     assert np.array_equal(bits16(Yd), exp)
+
+
+# ------------------------------------------------------------------ seeded random shapes
+def _random_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    cases = []
+    for _ in range(n):
+        N = int(rng.integers(2, 9))
+        K = 128 * N * int(rng.integers(1, 3))                # K and K' = 256 (N-1) r are whole numbers of 128-byte units
+        M = int(rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 255, 256, 257, 300, 511]))
+        O = int(rng.choice([1, 31, 32, 33, 127, 128, 129, 255, 256, 257, 384, 513, 700]))
+        cases.append((N, M, O, K))
+    return cases
+
+
+@pytest.mark.parametrize("N,M,O,K", _random_cases(24, seed=2024))
+def test_random_shapes_int8_end_to_end(N, M, O, K):
+    """The whole path on ragged shapes around every tile, fragment and token-block boundary, for every
+    pattern N = 2..8: prune + quantise, decompose, lift + quantise, sparse GEMM, dense GEMM; all bit-exact."""
+    X = synth.activations(M, K, seed=M + O + K, n_outliers=2)
+    W = synth.weights(O, K, seed=M + O + N)
+    ref = so.linear_reference(X, W, N, "i8")
+    Xd, Wd = dev(X), dev(W)
+    Wq, s_w = binding.slide_prune_quant(Wd, N, "i8")
+    assert np.array_equal(host(Wq), ref["Wq"]) and np.array_equal(host(s_w), ref["s_w"])
+    w_vals, w_meta, viol = binding.slide_decompose(Wq, N, "i8", count_violations=True)
+    XL, s_x = binding.act_lift_quant(Xd, N, "i8")
+    assert np.array_equal(host(XL), so.lift(ref["Xq"], N)) and np.array_equal(host(s_x), ref["s_x"])
+    Y = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, "i8")
+    assert int(host(viol)[0]) == 0
+    assert np.array_equal(bits16(Y), ref["Y"])
+    Xq, s_x2 = binding.act_lift_quant(Xd, 2, "i8")
+    Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, "i8")
+    assert np.array_equal(bits16(Yd), ref["Y"])
+
+
+@pytest.mark.parametrize("dtype", ["fp8", "bf16"])
+@pytest.mark.parametrize("N,M,O,K", _random_cases(8, seed=77))
+def test_random_shapes_float_end_to_end(dtype, N, M, O, K):
+    X = synth.activations(M, K, seed=M + O + K, n_outliers=2)
+    W = synth.weights(O, K, seed=M + O + N)
+    ref = so.linear_reference(X, W, N, dtype)
+    Xd, Wd = dev(X), dev(W)
+    Wq, s_w = binding.slide_prune_quant(Wd, N, dtype)
+    assert np.array_equal(from_dev_q(Wq, dtype), ref["Wq"])
+    w_vals, w_meta = binding.slide_decompose(Wq, N, dtype)
+    XL, s_x = binding.act_lift_quant(Xd, N, dtype)
+    assert np.array_equal(from_dev_q(XL, dtype), so.lift(ref["Xq"], N))
+    _float_gemm_check(bits16(binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype)), ref, dtype)
+    Xq, s_x2 = binding.act_lift_quant(Xd, 2, dtype)
+    _float_gemm_check(bits16(binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype)), ref, dtype)
