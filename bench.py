@@ -46,6 +46,9 @@ def parse():
     ap.add_argument("--native-2-4", action="store_true",
                     help="also time the same GEMM kernel on native 2:4 weights (N = 2) and report the paper's efficiency metric "
                          "(off by default so that a profiler's per-kernel averages of the default run cover the 6:8 launches only)")
+    ap.add_argument("--vendor-baseline", action="store_true",
+                    help="context only: also time torch._int_mm (the vendor library's INT8 GEMM, int32 output, no scale epilogue) on "
+                         "the four layer shapes")
     ap.add_argument("--sweep", choices=["dtypes_m", "patterns", "llama_block"], default=None,
                     help="instead of the headline step, time one of the other benchmark configurations and print its table "
                          "as one JSON line: dtypes_m = INT8/FP8/BF16 at M in {1,16,128,8192} on the Qwen2.5-7B shapes; "
@@ -289,6 +292,22 @@ def main():
         "roofline_lift": {"bound": "hbm", "achieved": lift_bytes / (lift_ms * 1e-3) * 1e-9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
                           "frac": lift_bytes / (lift_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, "kernel": "k_act_lift_quant (fp32 in, int8 out)"},
     }
+    if args.vendor_baseline:
+        vend = {}
+        for st in state:
+            a, bt = st["Xq"], st["Wq"].t()
+            for _ in range(3):
+                torch._int_mm(a, bt)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(20):
+                torch._int_mm(a, bt)
+            e1.record()
+            torch.cuda.synchronize()
+            vend[st["name"]] = e0.elapsed_time(e1) / 20
+        out["vendor_int8_gemm_ms"] = vend
+        out["vendor_int8_gemm_total_ms"] = sum(vend.values())
+        out["speedup_gemm_vs_vendor_dense"] = sum(vend.values()) / gemm_ms
     if g24_ms is not None:
         # Sec. 5 efficiency: measured speed-up over what native 2:4 on the same kernels predicts, S_2:4 / gamma
         out["native_2_4_gemm_ms"] = g24_ms
