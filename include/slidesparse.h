@@ -48,7 +48,8 @@ typedef enum {
 typedef enum {
     SS_I8 = 0,        /* int8, symmetric, Qmax = 127, int32 accumulation                      */
     SS_FP8_E4M3 = 1,  /* OCP e4m3fn byte, Qmax = 448, fp32 accumulation                       */
-    SS_BF16 = 2       /* bfloat16, unscaled, fp32 accumulation                                */
+    SS_BF16 = 2,      /* bfloat16, unscaled, fp32 accumulation                                */
+    SS_FP16 = 3       /* IEEE half, unscaled, fp32 accumulation (finite values within +-65504) */
 } ss_dtype;
 
 /* storage type of the un-quantised activations / weights handed to the quantisers */
@@ -71,14 +72,14 @@ ss_status slide_packed_sizes(int64_t O, int64_t K, int N, ss_dtype dtype,
  * channel symmetric quantisation as in Alg. 1 pass 1): for every row o of W[O,K] keep the
  * 2N-2 largest-|w| entries of each aligned run of 2N (ties keep the lower index), then
  * s_w[o] = max|w|/Qmax and Wq = clamp(rne(w * (Qmax/max|w|))) (BF16: rne to bf16, s_w
- * untouched and may be NULL).  W is fp32 or bf16 (in_dtype).  An all-zero row gets
- * s_w = 1. */
+ * untouched and may be NULL; FP16 likewise with rne to half).  W is fp32 or bf16
+ * (in_dtype).  An all-zero row gets s_w = 1. */
 ss_status slide_prune_quant(const void* W, ss_act_dtype in_dtype, int64_t O, int64_t K, int N,
                             ss_dtype dtype, void* Wq, float* s_w, void* stream);
 
 /* Sliding Window Decomposition + 2:4 compression (Sec. 3.2, Alg. 2; Sec. 4.3).
  * Wq[O,K] holds quantised weights obeying the (2N-2):2N pattern (at most 2N-2 non-zeros
- * per aligned run of 2N along K; +-0 count as zero for fp8/bf16).  Each 2N block is
+ * per aligned run of 2N along K; +-0 count as zero for fp8/bf16/fp16).  Each 2N block is
  * rewritten as N-1 stride-2 windows of 4 by the greedy residual allocation (window order
  * g, l ascending; inside a window the first <=2 unused non-zeros in ascending position),
  * every window is stored as 2 values + two 2-bit positions, and the result is laid out
@@ -99,8 +100,8 @@ ss_status slide_decompose_canonical(const void* Wq, int64_t O, int64_t K, int N,
 /* Fused quantisation + slide (Alg. 1).  X[M,K] with row stride ldx (elements), fp32 or
  * bf16.  Per token i: a = max_k |x|, s_x[i] = a/Qmax, r = Qmax/a (fp32), and for every
  * output window j = g(N-1)+l the four elements at b = 2N g + 2l are quantised as
- * clamp(rne(x*r), +-Qmax) and stored at X_lifted[i, 4j .. 4j+3].  out = SS_BF16: no
- * scaling, elements are rounded (rne) to bf16 and s_x may be NULL.  N = 2 is plain
+ * clamp(rne(x*r), +-Qmax) and stored at X_lifted[i, 4j .. 4j+3].  out = SS_BF16 / SS_FP16: no
+ * scaling, elements are rounded (rne) to bf16 / half and s_x may be NULL.  N = 2 is plain
  * per-token quantisation (K' = K).  An all-zero token gets s_x = 1 and zeros.
  * X_lifted is [M, K'] dense.  Requires K % 2N == 0. */
 ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_t K, int64_t ldx,
@@ -108,7 +109,7 @@ ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_
 
 /* 2:4 sparse GEMM over the lifted width (Sec. 4.3) with the scale epilogue:
  *   Y[m,o] = bf16( (fp32(acc[m,o]) * s_x[m]) * s_w[o] ),  acc = sum over K' of X' . W'
- * (SS_BF16: Y = bf16(acc), s_x and s_w ignored and may be NULL).  X_lifted[M,K_lifted]
+ * (SS_BF16, SS_FP16: Y = bf16(acc), s_x and s_w ignored and may be NULL).  X_lifted[M,K_lifted]
  * dense row-major from act_lift_quant; w_vals/w_meta from slide_decompose for the same
  * O and K_lifted.  Y is bf16 [M,O] with row stride ldy (elements, O <= ldy < 2^22).  INT8 accumulates
  * in int32 (exact), FP8 and BF16 in fp32 in the order of the matrix instructions.

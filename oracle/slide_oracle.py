@@ -74,6 +74,17 @@ def bf16_to_f32(b: np.ndarray) -> np.ndarray:
     return (np.asarray(b, dtype=np.uint16).astype(np.uint32) << 16).view(np.float32)
 
 
+def fp16_bits(x: np.ndarray) -> np.ndarray:
+    """fp32 -> IEEE binary16 bit pattern (uint16), round-to-nearest-even (numpy's conversion);
+    values beyond +-65504 are not in contract."""
+    return np.asarray(x, dtype=np.float32).astype(np.float16).view(np.uint16)
+
+
+def fp16_to_f32(b: np.ndarray) -> np.ndarray:
+    """binary16 bit pattern (uint16) -> fp32, exact."""
+    return np.asarray(b, dtype=np.uint16).view(np.float16).astype(np.float32)
+
+
 def fp8_e4m3_decode(code: np.ndarray) -> np.ndarray:
     """OCP e4m3fn byte -> fp64 value.  1 sign, 4 exponent (bias 7), 3 mantissa bits;
     no infinities; exponent 15 with mantissa 7 is NaN; largest finite value 448."""
@@ -111,7 +122,8 @@ def fp8_e4m3_encode(x: np.ndarray) -> np.ndarray:
 
 
 QMAX = {"i8": 127.0, "fp8": 448.0}
-DTYPES = ("i8", "fp8", "bf16")
+DTYPES = ("i8", "fp8", "bf16", "fp16")
+UNSCALED = ("bf16", "fp16")          # 16-bit operands carry no scales (App. D.1 lists BF16 and FP16 side by side)
 
 
 def to_real(q: np.ndarray, dtype: str) -> np.ndarray:
@@ -122,6 +134,8 @@ def to_real(q: np.ndarray, dtype: str) -> np.ndarray:
         return fp8_e4m3_decode(q)
     if dtype == "bf16":
         return bf16_to_f32(q).astype(np.float64)
+    if dtype == "fp16":
+        return fp16_to_f32(q).astype(np.float64)
     raise ValueError(dtype)
 
 
@@ -132,7 +146,7 @@ def is_zero(q: np.ndarray, dtype: str) -> np.ndarray:
         return np.asarray(q) == 0
     if dtype == "fp8":
         return (np.asarray(q, dtype=np.uint8) & 0x7F) == 0
-    if dtype == "bf16":
+    if dtype in UNSCALED:
         return (np.asarray(q, dtype=np.uint16) & 0x7FFF) == 0
     raise ValueError(dtype)
 
@@ -182,6 +196,8 @@ def quantize_rows(V: np.ndarray, dtype: str):
     V = np.asarray(V, dtype=np.float32)
     if dtype == "bf16":
         return bf16_bits(V), None
+    if dtype == "fp16":
+        return fp16_bits(V), None
     r, s = row_scales(V, dtype)
     prod = (V * r[:, None]).astype(np.float32)                 # one rounded fp32 multiply
     qmax = np.float32(QMAX[dtype])
@@ -322,7 +338,7 @@ def epilogue(acc: np.ndarray, s_x, s_w, dtype: str) -> np.ndarray:
         a = np.asarray(acc)
         assert np.all(np.abs(a) < 2 ** 31), "accumulator exceeds int32"
     f = np.asarray(acc).astype(np.float32)
-    if dtype != "bf16":
+    if dtype not in UNSCALED:
         f = (f * np.asarray(s_x, dtype=np.float32)[:, None]).astype(np.float32)
         f = (f * np.asarray(s_w, dtype=np.float32)[None, :]).astype(np.float32)
     return bf16_bits(f)

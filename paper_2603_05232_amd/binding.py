@@ -14,9 +14,9 @@ import torch
 _PKG = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_PKG, "libslidesparse.so")
 
-SS_I8, SS_FP8_E4M3, SS_BF16 = 0, 1, 2
+SS_I8, SS_FP8_E4M3, SS_BF16, SS_FP16 = 0, 1, 2, 3
 SS_IN_F32, SS_IN_BF16 = 0, 1
-DTYPE_CODE = {"i8": SS_I8, "fp8": SS_FP8_E4M3, "bf16": SS_BF16}
+DTYPE_CODE = {"i8": SS_I8, "fp8": SS_FP8_E4M3, "bf16": SS_BF16, "fp16": SS_FP16}
 EXPORTS = ("slide_lifted_k", "slide_packed_sizes", "slide_prune_quant", "slide_decompose",
            "slide_decompose_canonical", "act_lift_quant", "slide_sparse_gemm", "dense_gemm",
            "ss_status_string", "slide_format_version")
@@ -84,7 +84,7 @@ def _in_code(t: torch.Tensor) -> int:
 
 
 def _storage_dtype(dtype: str) -> torch.dtype:
-    return {"i8": torch.int8, "fp8": torch.uint8, "bf16": torch.bfloat16}[dtype]
+    return {"i8": torch.int8, "fp8": torch.uint8, "bf16": torch.bfloat16, "fp16": torch.float16}[dtype]
 
 
 def slide_lifted_k(K: int, N: int) -> int:
@@ -102,7 +102,7 @@ def slide_prune_quant(W: torch.Tensor, N: int, dtype: str):
     O, K = W.shape
     assert W.is_cuda and W.is_contiguous()
     Wq = torch.empty((O, K), dtype=_storage_dtype(dtype), device=W.device)
-    s_w = None if dtype == "bf16" else torch.empty((O,), dtype=torch.float32, device=W.device)
+    s_w = None if dtype in ("bf16", "fp16") else torch.empty((O,), dtype=torch.float32, device=W.device)
     _check(load().slide_prune_quant(_ptr(W), _in_code(W), O, K, N, DTYPE_CODE[dtype], _ptr(Wq), _ptr(s_w), _stream()),
            "slide_prune_quant")
     return Wq, s_w
@@ -145,7 +145,7 @@ def act_lift_quant(X: torch.Tensor, N: int, dtype: str, out=None, s_x=None):
         raise SlideSparseError(3 if 2 <= N <= 8 else 2, "act_lift_quant")
     if out is None:
         out = torch.empty((M, Kp), dtype=_storage_dtype(dtype), device=X.device)
-    if s_x is None and dtype != "bf16":
+    if s_x is None and dtype not in ("bf16", "fp16"):
         s_x = torch.empty((M,), dtype=torch.float32, device=X.device)
     ldx = X.stride(0) if M > 1 else K
     _check(load().act_lift_quant(_ptr(X), _in_code(X), M, K, ldx, N, DTYPE_CODE[dtype], _ptr(out), _ptr(s_x), _stream()),

@@ -111,7 +111,7 @@ using namespace ss;
 static ss_status check_decompose(int64_t O, int64_t K, int N, ss_dtype dtype)
 {
     if (!valid_N(N)) return SS_ERR_BAD_PATTERN_N;
-    if (dtype != SS_I8 && dtype != SS_FP8_E4M3 && dtype != SS_BF16) return SS_ERR_DTYPE;
+    if (!valid_dtype(dtype)) return SS_ERR_DTYPE;
     if (O < 0 || K <= 0 || K % (2 * N) != 0 || K > (1 << 24) || O > (1 << 24)) return SS_ERR_SHAPE;
     return SS_OK;
 }
@@ -143,7 +143,7 @@ extern "C" ss_status slide_decompose(const void* Wq, int64_t O, int64_t K, int N
     const int64_t nslots = npanels * nsteps * FRAGS_PER_PANEL * 64;
     const dim3 grid((unsigned)((nslots + 255) / 256)), block(256);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dtype == SS_BF16)
+    if (elem_size(dtype) == 2)
         hipLaunchKernelGGL(k_decompose_packed<2>, grid, block, 0, s, static_cast<const uint16_t*>(Wq), O, (int)K, N, true,
                            static_cast<uint4*>(w_vals), static_cast<uint32_t*>(w_meta), nslots, nsteps, violations);
     else
@@ -163,7 +163,7 @@ extern "C" ss_status slide_decompose_canonical(const void* Wq, int64_t O, int64_
     const int64_t total = O * nwin;
     dim3 grid((unsigned)((total + 255) / 256)), block(256);
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (dtype == SS_BF16)
+    if (elem_size(dtype) == 2)
         hipLaunchKernelGGL(k_decompose_canonical<2>, grid, block, 0, s, static_cast<const uint16_t*>(Wq), O, (int)K, N, true,
                            static_cast<uint16_t*>(vals), idx, violations);
     else

@@ -608,12 +608,12 @@ static int persistent_grid(int ntiles)
 static ss_status check_gemm(const void* X, const float* s_x, const void* W, const float* s_w, int64_t M, int64_t O, int64_t K,
                             ss_dtype dtype, const void* Y, int64_t ldy)
 {
-    if (dtype != SS_I8 && dtype != SS_FP8_E4M3 && dtype != SS_BF16) return SS_ERR_DTYPE;
+    if (!valid_dtype(dtype)) return SS_ERR_DTYPE;
     if (M < 0 || O < 0 || K <= 0 || (K * elem_size(dtype)) % KSTEP != 0 || ldy < O || M > (1 << 24) || ldy >= (1 << 22) || K * elem_size(dtype) > (1 << 23))
         return SS_ERR_SHAPE;
     if (M == 0 || O == 0) return SS_OK;
     if (!X || !W || !Y) return SS_ERR_NULL;
-    if (dtype != SS_BF16 && (!s_x || !s_w)) return SS_ERR_NULL;
+    if (!unscaled(dtype) && (!s_x || !s_w)) return SS_ERR_NULL;
     if (((uintptr_t)X & 15) || ((uintptr_t)W & 15)) return SS_ERR_SHAPE;
     return SS_OK;
 }
@@ -655,6 +655,7 @@ extern "C" ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq
     case SS_I8: return launch_dense<SS_I8>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, tiles_o, tiles_t, grid, hs);
     case SS_FP8_E4M3: return launch_dense<SS_FP8_E4M3>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, tiles_o, tiles_t, grid, hs);
     case SS_BF16: return launch_dense<SS_BF16>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_FP16: return launch_dense<SS_FP16>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, tiles_o, tiles_t, grid, hs);
     }
     return SS_ERR_DTYPE;
 }
@@ -678,6 +679,7 @@ extern "C" ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, c
     case SS_I8: return launch_sparse<SS_I8>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
     case SS_FP8_E4M3: return launch_sparse<SS_FP8_E4M3>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
     case SS_BF16: return launch_sparse<SS_BF16>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_FP16: return launch_sparse<SS_FP16>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
     }
     return SS_ERR_DTYPE;
 }

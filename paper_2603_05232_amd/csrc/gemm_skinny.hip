@@ -369,6 +369,7 @@ ss_status launch_sparse_skinny(const void* XL, const float* s_x, const void* w_v
     case SS_I8: return launch_sparse_dt<SS_I8>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, stream);
     case SS_FP8_E4M3: return launch_sparse_dt<SS_FP8_E4M3>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, stream);
     case SS_BF16: return launch_sparse_dt<SS_BF16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, stream);
+    case SS_FP16: return launch_sparse_dt<SS_FP16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, stream);
     }
     return SS_ERR_DTYPE;
 }
@@ -380,6 +381,7 @@ ss_status launch_dense_skinny(const void* Xq, const float* s_x, const void* Wq, 
     case SS_I8: return launch_dense_dt<SS_I8>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, stream);
     case SS_FP8_E4M3: return launch_dense_dt<SS_FP8_E4M3>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, stream);
     case SS_BF16: return launch_dense_dt<SS_BF16>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, stream);
+    case SS_FP16: return launch_dense_dt<SS_FP16>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, stream);
     }
     return SS_ERR_DTYPE;
 }

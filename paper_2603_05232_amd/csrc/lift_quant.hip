@@ -42,7 +42,7 @@ __device__ inline float block_absmax(float v, float* red)
     return m;
 }
 
-// quantise one element: OUT 0 = int8, 1 = fp8 e4m3, 2 = bf16 (no scale)
+// quantise one element: OUT 0 = int8, 1 = fp8 e4m3, 2 = bf16 (no scale), 3 = half (no scale)
 template <int OUT> __device__ inline uint32_t quant1(float x, float r)
 {
     if constexpr (OUT == 0) {
@@ -53,8 +53,10 @@ template <int OUT> __device__ inline uint32_t quant1(float x, float r)
         float q = x * r;
         q = fminf(fmaxf(q, -448.0f), 448.0f);
         return f32_to_e4m3(q);
-    } else {
+    } else if constexpr (OUT == 2) {
         return f32_to_bf16_bits(x);
+    } else {
+        return f32_to_f16_bits(x);
     }
 }
 
@@ -64,7 +66,7 @@ template <typename TIN, int OUT, int MAXV>
 __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __restrict__ X, int64_t ldx, int K, int N,
                                                                 uint8_t* __restrict__ XL, float* __restrict__ s_x, int Kp)
 {
-    constexpr int ES = OUT == 2 ? 2 : 1;                 // output element bytes
+    constexpr int ES = OUT >= 2 ? 2 : 1;                 // output element bytes
     extern __shared__ uint32_t lds[];                     // K * ES bytes of quantised row + 8 bytes of slack (read, never used)
     __shared__ float red[LQ_THREADS / 64];
     const int64_t m = blockIdx.x;
@@ -83,18 +85,18 @@ __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __rest
             const int idx = t + i * LQ_THREADS;
             if (idx < nvec) {
                 v[i] = xv[idx];
-                if constexpr (OUT != 2) {
+                if constexpr (OUT < 2) {
                     float f[IV::N]; IV::unpack(v[i], f);
 #pragma unroll
                     for (int e = 0; e < IV::N; ++e) amax = fmaxf(amax, fabsf(f[e]));
                 }
             }
         }
-    } else if constexpr (OUT != 2) {
+    } else if constexpr (OUT < 2) {
         for (int k = t; k < K; k += LQ_THREADS) amax = fmaxf(amax, fabsf(load_scalar(x + k)));
     }
     float r = 0.0f;
-    if constexpr (OUT != 2) {
+    if constexpr (OUT < 2) {
         amax = block_absmax(amax, red);
         constexpr float QMAX = OUT == 0 ? 127.0f : 448.0f;
         float s = 1.0f;
@@ -187,7 +189,7 @@ static ss_status launch_lift(const void* X, int64_t M, int64_t K, int64_t ldx, i
 {
     typedef InVec<TIN> IV;
     const int Kp = (int)lifted_k(K, N);
-    const int ES = OUT == 2 ? 2 : 1;
+    const int ES = OUT >= 2 ? 2 : 1;
     const size_t lds_bytes = (size_t)K * ES + 8;
     const bool vec_ok = (K % IV::N == 0) && (ldx % IV::N == 0) && (((uintptr_t)X & 15) == 0) && (((uintptr_t)XL & 15) == 0);
     const int64_t per_thread = (K / IV::N + LQ_THREADS - 1) / LQ_THREADS;
@@ -210,13 +212,13 @@ template <typename TIN, int OUT>
 __global__ __launch_bounds__(LQ_THREADS) void k_prune_quant(const TIN* __restrict__ W, int K, int N, uint8_t* __restrict__ Wq,
                                                              float* __restrict__ s_w)
 {
-    constexpr int ES = OUT == 2 ? 2 : 1;
+    constexpr int ES = OUT >= 2 ? 2 : 1;
     __shared__ float red[LQ_THREADS / 64];
     const int64_t o = blockIdx.x;
     const TIN* w = W + o * (int64_t)K;
     const int t = threadIdx.x;
     float r = 0.0f;
-    if constexpr (OUT != 2) {
+    if constexpr (OUT < 2) {
         float amax = 0.0f;
         for (int k = t; k < K; k += LQ_THREADS) amax = fmaxf(amax, fabsf(load_scalar(w + k)));
         amax = block_absmax(amax, red);               // the row maximum always survives pruning
@@ -265,19 +267,21 @@ extern "C" ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_
     if (!valid_N(N)) return SS_ERR_BAD_PATTERN_N;
     if (M < 0 || K <= 0 || K % (2 * N) != 0 || ldx < K || K > (1 << 24) || M > 0x7FFFFFFF) return SS_ERR_SHAPE;
     if (in_dtype != SS_IN_F32 && in_dtype != SS_IN_BF16) return SS_ERR_DTYPE;
-    if (out != SS_I8 && out != SS_FP8_E4M3 && out != SS_BF16) return SS_ERR_DTYPE;
+    if (!valid_dtype(out)) return SS_ERR_DTYPE;
     if ((size_t)K * elem_size(out) + 8 > 64 * 1024) return SS_ERR_SHAPE;    // quantised row must fit in LDS
     if (M == 0) return SS_OK;
-    if (!X || !X_lifted || (out != SS_BF16 && !s_x)) return SS_ERR_NULL;
+    if (!X || !X_lifted || (!unscaled(out) && !s_x)) return SS_ERR_NULL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (in_dtype == SS_IN_F32) {
         if (out == SS_I8) return launch_lift<float, 0>(X, M, K, ldx, N, X_lifted, s_x, st);
         if (out == SS_FP8_E4M3) return launch_lift<float, 1>(X, M, K, ldx, N, X_lifted, s_x, st);
-        return launch_lift<float, 2>(X, M, K, ldx, N, X_lifted, s_x, st);
+        if (out == SS_BF16) return launch_lift<float, 2>(X, M, K, ldx, N, X_lifted, s_x, st);
+        return launch_lift<float, 3>(X, M, K, ldx, N, X_lifted, s_x, st);
     }
     if (out == SS_I8) return launch_lift<uint16_t, 0>(X, M, K, ldx, N, X_lifted, s_x, st);
     if (out == SS_FP8_E4M3) return launch_lift<uint16_t, 1>(X, M, K, ldx, N, X_lifted, s_x, st);
-    return launch_lift<uint16_t, 2>(X, M, K, ldx, N, X_lifted, s_x, st);
+    if (out == SS_BF16) return launch_lift<uint16_t, 2>(X, M, K, ldx, N, X_lifted, s_x, st);
+    return launch_lift<uint16_t, 3>(X, M, K, ldx, N, X_lifted, s_x, st);
 }
 
 template <typename TIN, int OUT>
@@ -294,16 +298,18 @@ extern "C" ss_status slide_prune_quant(const void* W, ss_act_dtype in_dtype, int
     if (!valid_N(N)) return SS_ERR_BAD_PATTERN_N;
     if (O < 0 || K <= 0 || K % (2 * N) != 0 || K > (1 << 24) || O > 0x7FFFFFFF) return SS_ERR_SHAPE;
     if (in_dtype != SS_IN_F32 && in_dtype != SS_IN_BF16) return SS_ERR_DTYPE;
-    if (dtype != SS_I8 && dtype != SS_FP8_E4M3 && dtype != SS_BF16) return SS_ERR_DTYPE;
+    if (!valid_dtype(dtype)) return SS_ERR_DTYPE;
     if (O == 0) return SS_OK;
-    if (!W || !Wq || (dtype != SS_BF16 && !s_w)) return SS_ERR_NULL;
+    if (!W || !Wq || (!unscaled(dtype) && !s_w)) return SS_ERR_NULL;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (in_dtype == SS_IN_F32) {
         if (dtype == SS_I8) return launch_prune<float, 0>(W, O, K, N, Wq, s_w, st);
         if (dtype == SS_FP8_E4M3) return launch_prune<float, 1>(W, O, K, N, Wq, s_w, st);
-        return launch_prune<float, 2>(W, O, K, N, Wq, s_w, st);
+        if (dtype == SS_BF16) return launch_prune<float, 2>(W, O, K, N, Wq, s_w, st);
+        return launch_prune<float, 3>(W, O, K, N, Wq, s_w, st);
     }
     if (dtype == SS_I8) return launch_prune<uint16_t, 0>(W, O, K, N, Wq, s_w, st);
     if (dtype == SS_FP8_E4M3) return launch_prune<uint16_t, 1>(W, O, K, N, Wq, s_w, st);
-    return launch_prune<uint16_t, 2>(W, O, K, N, Wq, s_w, st);
+    if (dtype == SS_BF16) return launch_prune<uint16_t, 2>(W, O, K, N, Wq, s_w, st);
+    return launch_prune<uint16_t, 3>(W, O, K, N, Wq, s_w, st);
 }

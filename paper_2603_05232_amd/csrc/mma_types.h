@@ -42,6 +42,22 @@ template <> struct Mma<SS_BF16> {
     }
 };
 
+template <> struct Mma<SS_FP16> {
+    typedef v16f acc_t;
+    typedef v4i dfrag_t;
+    static constexpr int DENSE_SUB = 32;
+    static constexpr bool SCALED = false;
+    // same operand geometry as bf16 (checked by the parity tests against the oracle)
+    __device__ static acc_t sparse(v4i a, v8i b, acc_t c, int idx)
+    {
+        return __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v16h, b), c, idx, 0, 0);
+    }
+    __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c)
+    {
+        return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
+    }
+};
+
 // two fp32 -> packed bf16 (round to nearest even) in one v_cvt_pk_bf16_f32
 __device__ inline uint32_t pack_bf16x2(float a, float b)
 {

@@ -15,6 +15,8 @@ typedef float v4f __attribute__((ext_vector_type(4)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 typedef __bf16 v16bf __attribute__((ext_vector_type(16)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef _Float16 v16h __attribute__((ext_vector_type(16)));
 
 // Rows of the packed weight buffers are padded to this many output channels; one such
 // panel is the O-extent a wave accumulates, and the row order inside a panel is permuted
@@ -25,7 +27,9 @@ constexpr int KSTEP = 128;
 
 __host__ __device__ inline int64_t lifted_k(int64_t K, int N) { return (K / (2 * N)) * 4 * (N - 1); }
 inline bool valid_N(int N) { return N >= 2 && N <= 8; }
-inline int elem_size(ss_dtype d) { return d == SS_BF16 ? 2 : 1; }
+inline int elem_size(ss_dtype d) { return (d == SS_BF16 || d == SS_FP16) ? 2 : 1; }
+inline bool valid_dtype(ss_dtype d) { return d == SS_I8 || d == SS_FP8_E4M3 || d == SS_BF16 || d == SS_FP16; }
+inline bool unscaled(ss_dtype d) { return d == SS_BF16 || d == SS_FP16; }
 inline ss_status launch_status()
 {
     return hipGetLastError() == hipSuccess ? SS_OK : SS_ERR_HIP;
@@ -41,6 +45,9 @@ __device__ inline uint16_t f32_to_bf16_bits(float f)
     u += 0x7FFFu + ((u >> 16) & 1u);
     return (uint16_t)(u >> 16);
 }
+
+// fp32 -> IEEE half bits, round to nearest even (v_cvt_f16_f32)
+__device__ inline uint16_t f32_to_f16_bits(float f) { return __builtin_bit_cast(uint16_t, (_Float16)f); }
 
 // fp32 (already clamped to [-448, 448]) -> OCP e4m3fn byte, round to nearest even.
 __device__ inline uint32_t f32_to_e4m3(float f)

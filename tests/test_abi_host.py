@@ -51,6 +51,7 @@ def test_packed_sizes(lib):
     v, m = binding.slide_packed_sizes(512, 512, 4, "bf16")  # 2-byte values; one 4-byte index word per 16 value bytes
     assert (v, m) == (512 * 384 * 2, 512 * 96 * 2)
     assert binding.slide_packed_sizes(128, 128, 4, "bf16")[0] == 128 * 96 * 2   # K' = 192: 384 lifted bytes per row
+    assert binding.slide_packed_sizes(512, 512, 4, "fp16") == (v, m)
     with pytest.raises(binding.SlideSparseError) as e:
         binding.slide_packed_sizes(512, 520, 4, "i8")       # K' = 780 is not a multiple of 128
     assert e.value.code == 3

@@ -66,7 +66,7 @@ def test_llama3_8b_block_int8_m4096(name, K, O):
     assert torch.equal(Y, Yd)
 
 
-@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("M", [1, 16, 128])
 @pytest.mark.parametrize("name,K,O", [synth.QWEN25_7B[0], synth.QWEN25_7B[3]])
 def test_qwen25_7b_small_m(dtype, M, name, K, O):
@@ -79,7 +79,7 @@ def test_qwen25_7b_small_m(dtype, M, name, K, O):
         _float_gemm_check(sample(Yd), ref, dtype)
 
 
-@pytest.mark.parametrize("dtype", ["fp8", "bf16"])
+@pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("name,K,O", [synth.QWEN25_7B[0], synth.QWEN25_7B[3]])
 def test_qwen25_7b_float_m8192(dtype, name, K, O):
     Y, Yd, sample, ref = _run_and_sample(8192, K, O, 4, dtype, seed=7)

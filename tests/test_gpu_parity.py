@@ -31,17 +31,17 @@ def to_dev_q(q, dtype):
         return dev(q.astype(np.int8))
     if dtype == "fp8":
         return dev(q.astype(np.uint8))
-    return dev(q.astype(np.uint16).view(np.int16)).view(torch.bfloat16)
+    return dev(q.astype(np.uint16).view(np.int16)).view(torch.float16 if dtype == "fp16" else torch.bfloat16)
 
 
 def from_dev_q(t, dtype):
-    if dtype == "bf16":
+    if dtype in ("bf16", "fp16"):
         return bits16(t)
     return host(t)
 
 
 # ------------------------------------------------------------------ act_lift_quant
-@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("N,M,K", [(4, 16, 512), (2, 7, 64), (3, 5, 6 * 37), (4, 33, 3584), (5, 3, 5120), (8, 4, 16 * 9),
                                    (4, 2, 18944), (3, 9, 6144), (4, 3, 8 * 3001)])
 def test_act_lift_quant_fp32(dtype, N, M, K):
@@ -53,13 +53,13 @@ def test_act_lift_quant_fp32(dtype, N, M, K):
     got, gs = binding.act_lift_quant(dev(X), N, dtype)
     assert tuple(got.shape) == exp.shape
     assert np.array_equal(from_dev_q(got, dtype), exp)
-    if dtype == "bf16":
+    if dtype in ("bf16", "fp16"):
         assert gs is None
     else:
         assert np.array_equal(host(gs), s)
 
 
-@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
 def test_act_lift_quant_bf16_input_and_row_stride(dtype):
     M, K, N = 19, 1024, 4
     Xf = synth.activations(M, K, seed=5)
@@ -68,7 +68,7 @@ def test_act_lift_quant_bf16_input_and_row_stride(dtype):
     xt = dev(Xb.view(np.int16)).view(torch.bfloat16)
     got, gs = binding.act_lift_quant(xt, N, dtype)
     assert np.array_equal(from_dev_q(got, dtype), exp)
-    if dtype != "bf16":
+    if dtype not in ("bf16", "fp16"):
         assert np.array_equal(host(gs), s)
     # strided rows (a column slice of a wider matrix), fp32
     wide = np.zeros((M, K + 64), dtype=np.float32)
@@ -79,7 +79,7 @@ def test_act_lift_quant_bf16_input_and_row_stride(dtype):
 
 
 # ------------------------------------------------------------------ slide_prune_quant
-@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("N,O,K", [(4, 512, 512), (2, 9, 64), (3, 17, 6 * 50), (5, 6, 5120), (8, 5, 16 * 11)])
 def test_prune_quant(dtype, N, O, K):
     W = synth.weights(O, K, seed=N)
@@ -89,12 +89,12 @@ def test_prune_quant(dtype, N, O, K):
     expq, exps = so.prepare_weights(W, N, dtype)
     gq, gs = binding.slide_prune_quant(dev(W), N, dtype)
     assert np.array_equal(from_dev_q(gq, dtype), expq)
-    if dtype != "bf16":
+    if dtype not in ("bf16", "fp16"):
         assert np.array_equal(host(gs), exps)
 
 
 # ------------------------------------------------------------------ slide_decompose (canonical form)
-@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("N,O,K", [(4, 512, 512), (2, 5, 64), (3, 33, 6 * 21), (5, 7, 200), (6, 3, 120), (7, 2, 14 * 5), (8, 4, 160)])
 def test_decompose_canonical(dtype, N, O, K):
     W = synth.weights(O, K, seed=10 + N)
@@ -197,7 +197,7 @@ def _float_gemm_check(Ybits, ref, dtype):
     |Y - Y_ref| <= 2^-8 |Y_ref| + K 2^-23 ||Xd[m]|| ||Wd[o]||."""
     Xd = so.to_real(ref["Xq"], dtype)
     Wd = so.to_real(ref["Wq"], dtype)
-    if dtype != "bf16":
+    if dtype not in ("bf16", "fp16"):
         Xd = Xd * ref["s_x"].astype(np.float64)[:, None]
         Wd = Wd * ref["s_w"].astype(np.float64)[:, None]
     Yref = Xd @ Wd.T
@@ -210,7 +210,7 @@ def _float_gemm_check(Ybits, ref, dtype):
     assert np.all(err <= 2.0 ** -8 * np.abs(Yref) + K * 2.0 ** -23 * norm + 1e-30)
 
 
-@pytest.mark.parametrize("dtype", ["fp8", "bf16"])
+@pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("N,M,O,K", [(4, 16, 512, 512),           # the anchor shape
                                      (4, 300, 640, 1024),         # several tiles, ragged tokens and channels
                                      (3, 257, 130, 768),          # one ragged panel
@@ -244,7 +244,8 @@ def test_sparse_and_dense_gemm_float(dtype, N, M, O, K):
         Xq_i, Wq_i = so.fp8_e4m3_encode(Xi), so.fp8_e4m3_encode(Wi)
         sx = np.ones(M, np.float32); sw = np.ones(O, np.float32)
     else:
-        Xq_i, Wq_i = so.bf16_bits(Xi), so.bf16_bits(Wi)
+        to_bits = so.bf16_bits if dtype == "bf16" else so.fp16_bits
+        Xq_i, Wq_i = to_bits(Xi), to_bits(Wi)
         sx = sw = None
     exp = so.epilogue(so.gemm_exact(Xq_i, Wq_i, dtype), sx, sw, dtype)
     Wq_t = to_dev_q(Wq_i, dtype)
@@ -313,7 +314,7 @@ def test_random_shapes_int8_end_to_end(N, M, O, K):
     assert np.array_equal(bits16(Yd), ref["Y"])
 
 
-@pytest.mark.parametrize("dtype", ["fp8", "bf16"])
+@pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("N,M,O,K", _random_cases(8, seed=77))
 def test_random_shapes_float_end_to_end(dtype, N, M, O, K):
     X = synth.activations(M, K, seed=M + O + K, n_outliers=2)

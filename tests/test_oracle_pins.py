@@ -79,6 +79,22 @@ def test_bf16_rounding_matches_torch():
     assert np.array_equal(so.bf16_to_f32(ours), torch.from_numpy(x).to(torch.bfloat16).float().numpy())
 
 
+def test_fp16_rounding_matches_torch_and_the_format():
+    rng = np.random.default_rng(8)
+    x = (rng.standard_normal(300000) * np.exp(rng.uniform(-18, 10, 300000))).astype(np.float32)
+    x = np.clip(x, -65504, 65504)
+    x = np.concatenate([x, np.float32([0, -0.0, 1.0, 1.00048828125, 1.0009765625, 65504.0, 6.0e-8, 5.96e-8, 2.0e-8])])
+    ours = so.fp16_bits(x)
+    theirs = torch.from_numpy(x).to(torch.float16).view(torch.int16).numpy().view(np.uint16)
+    assert np.array_equal(ours, theirs)
+    # format facts: 1 + 2^-11 is a tie and goes to even (1.0); 1 + 2^-10 is representable; the largest finite value
+    assert ours[-7] == 0x3C00 and ours[-6] == 0x3C00 and ours[-5] == 0x3C01 and ours[-4] == 0x7BFF
+    assert so.fp16_to_f32(np.uint16([0x3C00, 0xC000, 0x0001, 0x7BFF])).tolist() == [1.0, -2.0, 2.0 ** -24, 65504.0]
+    # every finite code survives a round trip
+    codes = np.arange(0x7C00, dtype=np.uint16)
+    assert np.array_equal(so.fp16_bits(so.fp16_to_f32(codes)), codes)
+
+
 # ---------------------------------------------------------------- pruning
 @pytest.mark.parametrize("N", [2, 3, 4, 5, 8])
 def test_prune_keeps_top_2n_minus_2(N):
@@ -156,6 +172,9 @@ def test_fp8_and_bf16_quantisation():
     b, sb = so.quantize_rows(X, "bf16")
     assert sb is None
     assert np.array_equal(b, torch.from_numpy(X).to(torch.bfloat16).view(torch.int16).numpy().view(np.uint16))
+    h, sh = so.quantize_rows(X, "fp16")
+    assert sh is None
+    assert np.array_equal(h, torch.from_numpy(X).to(torch.float16).view(torch.int16).numpy().view(np.uint16))
 
 
 # ---------------------------------------------------------------- Phi (Alg. 2)
@@ -250,6 +269,8 @@ def test_alg2_multi_group_rows_and_identity():
     # fp8 / bf16: -0 counts as zero
     Wb = np.uint16([[0x8000, 0x3F80, 0, 0x3F80, 0x3F80, 0x8000]])
     assert so.slide_decompose(Wb, 3, "bf16").tolist() == [[0, 0x3F80, 0, 0x3F80, 0, 0, 0x3F80, 0]]
+    Wh = np.uint16([[0x8000, 0x3C00, 0, 0x3C00, 0x3C00, 0x8000]])     # -0, 1, 0, 1, 1, -0 in binary16
+    assert so.slide_decompose(Wh, 3, "fp16").tolist() == [[0, 0x3C00, 0, 0x3C00, 0, 0, 0x3C00, 0]]
 
 
 # ---------------------------------------------------------------- canonical 2:4 compression
@@ -325,7 +346,7 @@ def test_lifted_product_equals_unlifted_int8():
         assert ref["acc"][m, o] == sum(int(a) * int(b) for a, b in zip(ref["Xq"][m], ref["Wq"][o]))
 
 
-@pytest.mark.parametrize("dt", ["fp8", "bf16"])
+@pytest.mark.parametrize("dt", ["fp8", "bf16", "fp16"])
 def test_lifted_product_equals_unlifted_float(dt):
     N, K = 4, 256
     X = synth.activations(10, K, 2, n_outliers=2)
