@@ -8,7 +8,7 @@ cpu_baseline leg.  Nothing in the product package may import it.
 Notation (fixed for the whole repository; the paper reuses letters):
     M   tokens                      K   input features
     O   output features             N   pattern parameter, pattern is (2N-2):2N
-    nw = N-1 windows per 2N block   K' = K * 2(N-1)/N   lifted width
+    nw = N-1 windows per 2N block   K' = ceil(K/2N) * 4(N-1)  lifted width (= K * 2(N-1)/N when 2N | K)
     X[M,K], W[O,K], Y[M,O] all row-major;  Y = X . W^T
 
 Every function cites the passage of the paper that defines it.  Floating-point
@@ -44,12 +44,32 @@ def s_eff(N: int, alpha: float = 2.0) -> float:
     return alpha / gamma(N)
 
 
-def lifted_k(K: int, N: int) -> int:
-    """K' = (K/2N) * 4(N-1); K must be a multiple of 2N (Alg. 2 uses K/2N groups)."""
+def n_groups(K: int, N: int) -> int:
+    """n_g = ceil(K / 2N): the last block is completed with zeros when 2N does not
+    divide K (Alg. 1, the line that sets n_g and n_w)."""
     _check_N(N)
-    if K <= 0 or K % (2 * N) != 0:
-        raise ValueError(f"K={K} is not a positive multiple of 2N={2 * N}")
-    return (K // (2 * N)) * 4 * (N - 1)
+    if K <= 0:
+        raise ValueError(f"K={K} is not positive")
+    return -(-K // (2 * N))
+
+
+def lifted_k(K: int, N: int) -> int:
+    """K' = 4 n_w = n_g * 4(N-1) (Alg. 1: Y has 4 n_w columns)."""
+    return n_groups(K, N) * 4 * (N - 1)
+
+
+def pad_blocks(A: np.ndarray, N: int) -> np.ndarray:
+    """A[R, K] -> A[R, n_g * 2N] with zero columns appended: the zero-completed last
+    block that Alg. 1's n_g = ceil(K/2N) implies.  Zero of every storage type here
+    is the all-zero bit pattern."""
+    A = np.asarray(A)
+    R, K = A.shape
+    Kb = n_groups(K, N) * 2 * N
+    if Kb == K:
+        return A
+    out = np.zeros((R, Kb), dtype=A.dtype)
+    out[:, :K] = A
+    return out
 
 
 def _check_N(N: int) -> None:
@@ -157,18 +177,19 @@ def is_zero(q: np.ndarray, dtype: str) -> np.ndarray:
 
 def prune_2n(W: np.ndarray, N: int) -> np.ndarray:
     """Keep the 2N-2 largest-|w| entries of every aligned run of 2N along K, zero
-    the other two.  Ties in |w|: the lower index is kept."""
+    the other two.  Ties in |w|: the lower index is kept.  A last run shorter than
+    2N is completed with zeros first (they are the first to be dropped) and cut
+    back afterwards."""
     _check_N(N)
     W = np.asarray(W)
     O, K = W.shape
-    if K % (2 * N):
-        raise ValueError("K not a multiple of 2N")
-    blk = W.reshape(O, K // (2 * N), 2 * N)
+    Wb = pad_blocks(W, N)
+    blk = Wb.reshape(O, Wb.shape[1] // (2 * N), 2 * N)
     order = np.argsort(-np.abs(blk), axis=-1, kind="stable")   # descending |w|, stable
     drop = order[..., 2 * N - 2:]                              # the two smallest
     out = blk.copy()
     np.put_along_axis(out, drop, 0, axis=-1)
-    return out.reshape(O, K)
+    return out.reshape(O, -1)[:, :K]
 
 
 # ----------------------------------------------------------------------------
@@ -227,8 +248,8 @@ def slide_decompose(Wq: np.ndarray, N: int, dtype: str = "i8") -> np.ndarray:
     Wq = np.asarray(Wq)
     O, K = Wq.shape
     Kp = lifted_k(K, N)
-    ng = K // (2 * N)
-    blk = Wq.reshape(O, ng, 2 * N)
+    ng = n_groups(K, N)
+    blk = pad_blocks(Wq, N).reshape(O, ng, 2 * N)       # last block zero-completed
     nz = ~is_zero(blk, dtype)
     if np.any(nz.sum(axis=-1) > 2 * N - 2):
         raise ValueError("a 2N block holds more than 2N-2 non-zeros")
@@ -295,11 +316,13 @@ def decompress_24(vals: np.ndarray, idx: np.ndarray) -> np.ndarray:
 # ----------------------------------------------------------------------------
 
 def lift(Xq: np.ndarray, N: int) -> np.ndarray:
-    """X'[i, 4 j + t] = X[i, 2N g + 2 l + t],  j = g (N-1) + l,  t = 0..3."""
+    """X'[i, 4 j + t] = X[i, 2N g + 2 l + t],  j = g (N-1) + l,  t = 0..3; source
+    columns at or beyond K (last block when 2N does not divide K) read as zero."""
     _check_N(N)
     Xq = np.asarray(Xq)
     M, K = Xq.shape
     Kp = lifted_k(K, N)
+    Xq = pad_blocks(Xq, N)
     out = np.empty((M, Kp), dtype=Xq.dtype)
     for j in range(Kp // 4):
         g, l = divmod(j, N - 1)

@@ -40,8 +40,12 @@ def test_lifted_k_of_benchmark_shapes():
     assert so.lifted_k(6144, 3) == 8192 and so.lifted_k(4096, 4) == 6144 and so.lifted_k(5120, 5) == 8192
     for N in range(2, 9):
         assert so.lifted_k(2 * N * 7, N) == 7 * 4 * (N - 1)
-        with pytest.raises(ValueError):
-            so.lifted_k(2 * N * 7 + 2, N)
+        # Alg. 1: n_g = ceil(K / 2N), so a partial last block counts as a whole one
+        assert so.lifted_k(2 * N * 7 + 2, N) == 8 * 4 * (N - 1)
+        assert so.lifted_k(1, N) == 4 * (N - 1)
+    assert so.lifted_k(3584, 3) == 598 * 8 and so.lifted_k(4096, 3) == 683 * 8 and so.lifted_k(6912, 5) == 692 * 16
+    with pytest.raises(ValueError):
+        so.lifted_k(0, 4)
     for bad in (1, 9, 0, -1):
         with pytest.raises(ValueError):
             so.lifted_k(64, bad)
@@ -392,3 +396,57 @@ def test_config1_end_to_end_consistency():
     exact = X.astype(np.float64) @ so.prune_2n(W, 4).astype(np.float64).T
     rel = np.linalg.norm(Yf - exact) / np.linalg.norm(exact)
     assert rel < 0.1
+
+
+# ---------------------------------------------------------------- K not a multiple of 2N
+@pytest.mark.parametrize("N", [2, 3, 4, 5, 8])
+def test_partial_last_block_equals_explicit_zero_padding(N):
+    """Alg. 1 sets n_g = ceil(K/2N): every step on a row whose length is not a multiple of
+    2N must equal the same step on the row completed with zeros (checked by padding
+    explicitly with numpy and calling the functions at a multiple of 2N), and the
+    lifted product must still equal the plain product over the original K."""
+    rng = np.random.default_rng(100 + N)
+    for r in range(1, 2 * N):
+        K = 2 * N * 3 + r
+        Kb = 2 * N * 4
+        W = rng.standard_normal((5, K)).astype(np.float32)
+        X = rng.standard_normal((4, K)).astype(np.float32)
+        Wpad = np.zeros((5, Kb), np.float32); Wpad[:, :K] = W
+        Xpad = np.zeros((4, Kb), np.float32); Xpad[:, :K] = X
+        # pruning: pads are dropped first, the result is the padded call cut back
+        P = so.prune_2n(W, N)
+        assert np.array_equal(P, so.prune_2n(Wpad, N)[:, :K])
+        tail = P[:, 2 * N * 3:]
+        kept = (tail != 0).sum(axis=1)
+        assert np.all(kept == min(r, 2 * N - 2))           # only a tail of 2N-1 loses a real entry
+        if r == 2 * N - 1:
+            lost = np.argmax(tail == 0, axis=1)
+            assert np.array_equal(lost, np.argmin(np.abs(W[:, 2 * N * 3:]), axis=1))
+        for dt in ("i8", "bf16"):
+            Wq, _ = so.quantize_rows(P, dt)
+            Wq_pad = np.zeros((5, Kb), Wq.dtype); Wq_pad[:, :K] = Wq
+            Wp = so.slide_decompose(Wq, N, dt)
+            assert Wp.shape == (5, 4 * 4 * (N - 1))
+            assert np.array_equal(Wp, so.slide_decompose(Wq_pad, N, dt))
+            Xl, sx = so.act_lift_quant(X, N, dt)
+            Xl_pad, sx_pad = so.act_lift_quant(Xpad, N, dt)
+            assert np.array_equal(Xl, Xl_pad)
+            assert sx is None or np.array_equal(sx, sx_pad)
+            Xq, _ = so.quantize_rows(X, dt)
+            lifted = so.gemm_exact(Xl, Wp, dt)
+            plain = so.gemm_exact(Xq, Wq, dt)
+            if dt == "i8":
+                assert np.array_equal(lifted, plain)
+            else:
+                assert np.allclose(lifted, plain, rtol=1e-12, atol=1e-12)
+
+
+def test_partial_last_block_hand_worked():
+    # 4:6 (N = 3), K = 8: one full block and a block of two real elements.
+    # block 1 = (7, 9, 0, 0, 0, 0) after zero completion; windows of block 1 read
+    # positions 6..9 and 8..11 -> (7, 9, 0, 0) and (0, 0, 0, 0)
+    W = np.int8([[1, 0, 2, 3, 0, 4, 7, 9]])
+    Wp = so.slide_decompose(W, 3, "i8")
+    assert Wp.tolist() == [[1, 0, 2, 0, 0, 3, 0, 4, 7, 9, 0, 0, 0, 0, 0, 0]]
+    X = np.int8([[10, 11, 12, 13, 14, 15, 16, 17]])
+    assert so.lift(X, 3).tolist() == [[10, 11, 12, 13, 12, 13, 14, 15, 16, 17, 0, 0, 0, 0, 0, 0]]
