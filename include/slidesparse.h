@@ -11,7 +11,9 @@
  *   dense GEMM at the original K, the baseline of every speed-up (Sec. 5.1)  -> dense_gemm
  *
  * Symbols: M tokens, K input features, O output features, N pattern parameter of
- * the (2N-2):2N pattern (N = 2 is native 2:4), K' the lifted width.
+ * the (2N-2):2N pattern (N = 2 is native 2:4), K' the lifted width, Kld >= K' the stored
+ * width of a lifted row (slide_lifted_ld).  K need not be a multiple of 2N: as in Alg. 1
+ * (n_g = ceil(K/2N)) the last block is completed with zeros.
  *
  * Conventions for every call
  *   - every data pointer is a DEVICE pointer owned by the caller; the library never
@@ -55,16 +57,23 @@ typedef enum {
 /* storage type of the un-quantised activations / weights handed to the quantisers */
 typedef enum { SS_IN_F32 = 0, SS_IN_BF16 = 1 } ss_act_dtype;
 
-/* K' = K * 2(N-1)/N, the lifted width (Sec. 3.4, expansion factor gamma = 2 - 2/N).
- * Returns -1 if N is outside 2..8 or K is not a positive multiple of 2N. */
+/* K' = 4 n_w = ceil(K/2N) * 4(N-1), the lifted width (Alg. 1; = K * 2(N-1)/N when 2N divides
+ * K: Sec. 3.4, expansion factor gamma = 2 - 2/N).  Returns -1 if N is outside 2..8 or K is
+ * outside 1..2^24. */
 int64_t slide_lifted_k(int64_t K, int N);
+
+/* Kld: the width, in elements, of the rows act_lift_quant writes and of the K_lifted argument
+ * of slide_sparse_gemm: K' rounded up to a whole number of 128-byte units (the k granularity
+ * of the GEMM kernels).  Columns K' .. Kld-1 of X_lifted are zero and the matching windows of
+ * the packed weights are empty, so they add nothing to the product.  Kld == K' for every
+ * benchmark shape of the paper's models at 6:8.  Returns -1 on a bad N, K or dtype. */
+int64_t slide_lifted_ld(int64_t K, int N, ss_dtype dtype);
 
 /* Byte sizes of the two buffers slide_decompose writes for an [O,K] weight matrix.
  * The packed layout is opaque (ordered for the sparse matrix instruction's operand and
  * index registers); rows are padded to a multiple of 128.  With b = bytes per element,
- * vals_bytes = Opad * K' * b / 2 ((N-1)/N of the dense weight bytes) and meta_bytes =
- * Opad * K' * b / 8 (one 4-byte index word per 16 bytes of values; (N-1)/(4N) of dense).
- * Requires K % 2N == 0 and K' * b % 128 == 0. */
+ * vals_bytes = Opad * Kld * b / 2 ((N-1)/N of the dense weight bytes when Kld = K') and
+ * meta_bytes = Opad * Kld * b / 8 (one 4-byte index word per 16 bytes of values). */
 ss_status slide_packed_sizes(int64_t O, int64_t K, int N, ss_dtype dtype,
                              size_t* vals_bytes, size_t* meta_bytes);
 
@@ -73,7 +82,8 @@ ss_status slide_packed_sizes(int64_t O, int64_t K, int N, ss_dtype dtype,
  * 2N-2 largest-|w| entries of each aligned run of 2N (ties keep the lower index), then
  * s_w[o] = max|w|/Qmax and Wq = clamp(rne(w * (Qmax/max|w|))) (BF16: rne to bf16, s_w
  * untouched and may be NULL; FP16 likewise with rne to half).  W is fp32 or bf16
- * (in_dtype).  An all-zero row gets s_w = 1. */
+ * (in_dtype).  An all-zero row gets s_w = 1.  A last run shorter than 2N is treated as
+ * completed with zeros, which are the first entries to be dropped. */
 ss_status slide_prune_quant(const void* W, ss_act_dtype in_dtype, int64_t O, int64_t K, int N,
                             ss_dtype dtype, void* Wq, float* s_w, void* stream);
 
@@ -83,15 +93,14 @@ ss_status slide_prune_quant(const void* W, ss_act_dtype in_dtype, int64_t O, int
  * rewritten as N-1 stride-2 windows of 4 by the greedy residual allocation (window order
  * g, l ascending; inside a window the first <=2 unused non-zeros in ascending position),
  * every window is stored as 2 values + two 2-bit positions, and the result is laid out
- * for slide_sparse_gemm.  Requires K % 2N == 0 and K' * sizeof(element) % 128 == 0
- * (SS_ERR_SHAPE otherwise).
+ * for slide_sparse_gemm (Kld wide; a last block shorter than 2N is completed with zeros).
  * violations (nullable, device int32, must be zeroed by the caller): incremented once
  * per 2N block that holds more than 2N-2 non-zeros; output is unspecified for such blocks. */
 ss_status slide_decompose(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype,
                           void* w_vals, void* w_meta, int32_t* violations, void* stream);
 
 /* Same decomposition in a plain, documented form for inspection and parity tests:
- * vals[O, K'/2] (dtype) and idx[O, K'/4] bytes, one per window = i0 | i1 << 2 with
+ * vals[O, K'/2] (dtype) and idx[O, K'/4] bytes (K', not Kld), one per window = i0 | i1 << 2 with
  * i0 < i1 the positions (0..3) of the two stored values; a window with fewer than two
  * non-zeros stores value 0 at the lowest positions not holding a non-zero. */
 ss_status slide_decompose_canonical(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype,
@@ -102,16 +111,18 @@ ss_status slide_decompose_canonical(const void* Wq, int64_t O, int64_t K, int N,
  * output window j = g(N-1)+l the four elements at b = 2N g + 2l are quantised as
  * clamp(rne(x*r), +-Qmax) and stored at X_lifted[i, 4j .. 4j+3].  out = SS_BF16 / SS_FP16: no
  * scaling, elements are rounded (rne) to bf16 / half and s_x may be NULL.  N = 2 is plain
- * per-token quantisation (K' = K).  An all-zero token gets s_x = 1 and zeros.
- * X_lifted is [M, K'] dense.  Requires K % 2N == 0. */
+ * per-token quantisation (K' = K rounded up to 4).  An all-zero token gets s_x = 1 and
+ * zeros.  Source columns at or beyond K read as zero.  X_lifted is [M, Kld] dense, 16-byte
+ * aligned (SS_ERR_SHAPE otherwise), columns K'..Kld-1 zero.  The quantised row is kept in
+ * on-chip memory: ceil(K/2N)*2N*sizeof(element) + 8 must not exceed 64 KiB. */
 ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_t K, int64_t ldx,
                          int N, ss_dtype out, void* X_lifted, float* s_x, void* stream);
 
 /* 2:4 sparse GEMM over the lifted width (Sec. 4.3) with the scale epilogue:
  *   Y[m,o] = bf16( (fp32(acc[m,o]) * s_x[m]) * s_w[o] ),  acc = sum over K' of X' . W'
  * (SS_BF16, SS_FP16: Y = bf16(acc), s_x and s_w ignored and may be NULL).  X_lifted[M,K_lifted]
- * dense row-major from act_lift_quant; w_vals/w_meta from slide_decompose for the same
- * O and K_lifted.  Y is bf16 [M,O] with row stride ldy (elements, O <= ldy < 2^22).  INT8 accumulates
+ * dense row-major from act_lift_quant (K_lifted = Kld); w_vals/w_meta from slide_decompose
+ * for the same O, K and N.  Y is bf16 [M,O] with row stride ldy (elements, O <= ldy < 2^22).  INT8 accumulates
  * in int32 (exact), FP8 and BF16 in fp32 in the order of the matrix instructions.
  * Requires K_lifted * sizeof(element) % 128 == 0 (and <= 2^23 bytes per row), M <= 2^24, and 16-byte
  * aligned operand pointers.  For M <= 64 (or M <= 128 with O < 16384) kernels that stream the weights once

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_PKG, "libslidesparse.so")
 SS_I8, SS_FP8_E4M3, SS_BF16, SS_FP16 = 0, 1, 2, 3
 SS_IN_F32, SS_IN_BF16 = 0, 1
 DTYPE_CODE = {"i8": SS_I8, "fp8": SS_FP8_E4M3, "bf16": SS_BF16, "fp16": SS_FP16}
-EXPORTS = ("slide_lifted_k", "slide_packed_sizes", "slide_prune_quant", "slide_decompose",
+EXPORTS = ("slide_lifted_k", "slide_lifted_ld", "slide_packed_sizes", "slide_prune_quant", "slide_decompose",
            "slide_decompose_canonical", "act_lift_quant", "slide_sparse_gemm", "dense_gemm",
            "ss_status_string", "slide_format_version")
 
@@ -41,6 +41,8 @@ def load():
     i64, i32, vp, sz = ctypes.c_int64, ctypes.c_int, ctypes.c_void_p, ctypes.c_size_t
     lib.slide_lifted_k.argtypes = [i64, i32]
     lib.slide_lifted_k.restype = i64
+    lib.slide_lifted_ld.argtypes = [i64, i32, i32]
+    lib.slide_lifted_ld.restype = i64
     lib.slide_packed_sizes.argtypes = [i64, i64, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.slide_prune_quant.argtypes = [vp, i32, i64, i64, i32, i32, vp, vp, vp]
     lib.slide_decompose.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
@@ -91,6 +93,10 @@ def slide_lifted_k(K: int, N: int) -> int:
     return int(load().slide_lifted_k(K, N))
 
 
+def slide_lifted_ld(K: int, N: int, dtype: str) -> int:
+    return int(load().slide_lifted_ld(K, N, DTYPE_CODE[dtype]))
+
+
 def slide_packed_sizes(O: int, K: int, N: int, dtype: str):
     v, m = ctypes.c_size_t(), ctypes.c_size_t()
     _check(load().slide_packed_sizes(O, K, N, DTYPE_CODE[dtype], ctypes.byref(v), ctypes.byref(m)), "slide_packed_sizes")
@@ -137,10 +143,10 @@ def slide_decompose_canonical(Wq: torch.Tensor, N: int, dtype: str):
 
 
 def act_lift_quant(X: torch.Tensor, N: int, dtype: str, out=None, s_x=None):
-    """X[M,K] fp32/bf16 (row stride allowed) -> (X_lifted[M,K'], s_x[M] or None)."""
+    """X[M,K] fp32/bf16 (row stride allowed) -> (X_lifted[M,Kld], s_x[M] or None)."""
     M, K = X.shape
     assert X.is_cuda and X.stride(1) == 1
-    Kp = slide_lifted_k(K, N)
+    Kp = slide_lifted_ld(K, N, dtype)
     if Kp < 0:
         raise SlideSparseError(3 if 2 <= N <= 8 else 2, "act_lift_quant")
     if out is None:
@@ -154,7 +160,7 @@ def act_lift_quant(X: torch.Tensor, N: int, dtype: str, out=None, s_x=None):
 
 
 def slide_sparse_gemm(X_lifted, s_x, w_vals, w_meta, s_w, O: int, dtype: str, out=None):
-    """Y[M,O] bf16 = epilogue(X_lifted[M,K'] . W'^T)."""
+    """Y[M,O] bf16 = epilogue(X_lifted[M,Kld] . W'^T)."""
     M, Kp = X_lifted.shape
     assert X_lifted.is_contiguous()
     if out is None:

@@ -13,15 +13,18 @@ template <> struct Elem<1> { typedef uint8_t T; __device__ static bool nz(T v, b
 template <> struct Elem<2> { typedef uint16_t T; __device__ static bool nz(T v, bool) { return (v & 0x7FFF) != 0; } };
 
 // One window of the decomposition: values and positions (i0 < i1) of window l of block g of a
-// row, plus the block's non-zero count.  `row` points at the row's first element.
+// row, plus the block's non-zero count.  `row` points at the row's first element, K is its
+// length: elements at and beyond K read as zero (last block completed with zeros, Alg. 1's
+// n_g = ceil(K / 2N)), and a block at or beyond n_g is all zero (padding of the stored width).
 template <int ES>
-__device__ inline void slide_window(const typename Elem<ES>::T* row, int N, int g, int l, bool fp,
+__device__ inline void slide_window(const typename Elem<ES>::T* row, int K, int N, int g, int l, bool fp,
                                     typename Elem<ES>::T& v0, typename Elem<ES>::T& v1, uint32_t& i0, uint32_t& i1, int& nnz)
 {
     typedef typename Elem<ES>::T T;
     const T* blk = row + (int64_t)g * 2 * N;
+    const int left = K - g * 2 * N;                      // elements of this block inside the row (may be <= 0)
     uint32_t nzmask = 0;
-    for (int p = 0; p < 2 * l + 4; ++p) nzmask |= (uint32_t)Elem<ES>::nz(blk[p], fp) << p;
+    for (int p = 0; p < 2 * l + 4; ++p) nzmask |= (uint32_t)(p < left && Elem<ES>::nz(blk[p], fp)) << p;
     uint32_t used = 0, taken = 0;
     for (int w = 0; w <= l; ++w) {                       // greedy, windows in ascending order
         int cnt = 0;
@@ -33,7 +36,7 @@ __device__ inline void slide_window(const typename Elem<ES>::T* row, int N, int 
     }
     if (l == 0) {                                        // pattern check, once per block
         uint32_t all = nzmask;
-        for (int p = 4; p < 2 * N; ++p) all |= (uint32_t)Elem<ES>::nz(blk[p], fp) << p;
+        for (int p = 4; p < 2 * N; ++p) all |= (uint32_t)(p < left && Elem<ES>::nz(blk[p], fp)) << p;
         nnz = __popc(all);
     } else nnz = 0;
     // pad to two positions with the lowest offsets that hold no stored non-zero
@@ -51,14 +54,14 @@ __global__ __launch_bounds__(256) void k_decompose_canonical(const typename Elem
                                                               typename Elem<ES>::T* __restrict__ vals, uint8_t* __restrict__ idx,
                                                               int32_t* __restrict__ violations)
 {
-    const int nwin = (K / (2 * N)) * (N - 1);
+    const int nwin = (int)n_groups(K, N) * (N - 1);
     const int64_t id = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (id >= O * nwin) return;
     const int64_t o = id / nwin;
     const int j = (int)(id - o * nwin);
     const int g = j / (N - 1), l = j - g * (N - 1);
     typename Elem<ES>::T v0, v1; uint32_t i0, i1; int nnz;
-    slide_window<ES>(Wq + o * (int64_t)K, N, g, l, fp, v0, v1, i0, i1, nnz);
+    slide_window<ES>(Wq + o * (int64_t)K, K, N, g, l, fp, v0, v1, i0, i1, nnz);
     vals[o * (int64_t)nwin * 2 + 2 * j] = v0;
     vals[o * (int64_t)nwin * 2 + 2 * j + 1] = v1;
     idx[o * (int64_t)nwin + j] = (uint8_t)(i0 | (i1 << 2));
@@ -92,7 +95,7 @@ __global__ __launch_bounds__(256) void k_decompose_packed(const typename Elem<ES
             const int j = step * (2 * NW) + step_window<ES>(qa, w);
             const int g = j / (N - 1), l = j - g * (N - 1);
             T v0, v1; uint32_t i0, i1; int nnz;
-            slide_window<ES>(Wq + o * (int64_t)K, N, g, l, fp, v0, v1, i0, i1, nnz);
+            slide_window<ES>(Wq + o * (int64_t)K, K, N, g, l, fp, v0, v1, i0, i1, nnz);
             if constexpr (ES == 1) v[w >> 1] |= ((uint32_t)v0 | ((uint32_t)v1 << 8)) << (16 * (w & 1));
             else v[w] = (uint32_t)v0 | ((uint32_t)v1 << 16);
             m |= (i0 | (i1 << 2)) << (4 * w);
@@ -112,7 +115,7 @@ static ss_status check_decompose(int64_t O, int64_t K, int N, ss_dtype dtype)
 {
     if (!valid_N(N)) return SS_ERR_BAD_PATTERN_N;
     if (!valid_dtype(dtype)) return SS_ERR_DTYPE;
-    if (O < 0 || K <= 0 || K % (2 * N) != 0 || K > (1 << 24) || O > (1 << 24)) return SS_ERR_SHAPE;
+    if (O < 0 || K <= 0 || K > (1 << 24) || O > (1 << 24)) return SS_ERR_SHAPE;
     return SS_OK;
 }
 
@@ -121,8 +124,7 @@ extern "C" ss_status slide_packed_sizes(int64_t O, int64_t K, int N, ss_dtype dt
     ss_status st = check_decompose(O, K, N, dtype);
     if (st != SS_OK) return st;
     if (!vals_bytes || !meta_bytes) return SS_ERR_NULL;
-    const int64_t Kpb = lifted_k(K, N) * elem_size(dtype);    // bytes of a lifted row
-    if (Kpb % KSTEP != 0) return SS_ERR_SHAPE;
+    const int64_t Kpb = lifted_ld(K, N, elem_size(dtype)) * elem_size(dtype);    // stored bytes of a lifted row
     const int64_t Opad = (O + PANEL - 1) / PANEL * PANEL;
     *vals_bytes = (size_t)(Opad * (Kpb / 2));
     *meta_bytes = (size_t)(Opad * (Kpb / 8));            // one 4-byte index word per 16 bytes of values
@@ -134,8 +136,7 @@ extern "C" ss_status slide_decompose(const void* Wq, int64_t O, int64_t K, int N
 {
     ss_status st = check_decompose(O, K, N, dtype);
     if (st != SS_OK) return st;
-    const int64_t Kpb = lifted_k(K, N) * elem_size(dtype);
-    if (Kpb % KSTEP != 0) return SS_ERR_SHAPE;
+    const int64_t Kpb = lifted_ld(K, N, elem_size(dtype)) * elem_size(dtype);
     if (O == 0) return SS_OK;
     if (!Wq || !w_vals || !w_meta) return SS_ERR_NULL;
     const int64_t npanels = (O + PANEL - 1) / PANEL;
@@ -159,7 +160,7 @@ extern "C" ss_status slide_decompose_canonical(const void* Wq, int64_t O, int64_
     if (st != SS_OK) return st;
     if (O == 0) return SS_OK;
     if (!Wq || !vals || !idx) return SS_ERR_NULL;
-    const int64_t nwin = (K / (2 * N)) * (N - 1);
+    const int64_t nwin = n_groups(K, N) * (N - 1);
     const int64_t total = O * nwin;
     dim3 grid((unsigned)((total + 255) / 256)), block(256);
     hipStream_t s = static_cast<hipStream_t>(stream);

@@ -64,10 +64,12 @@ template <int OUT> __device__ inline uint32_t quant1(float x, float r)
 // aligned rows).  MAXV == 0: scalar loads, second pass re-reads the row.
 template <typename TIN, int OUT, int MAXV>
 __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __restrict__ X, int64_t ldx, int K, int N,
-                                                                uint8_t* __restrict__ XL, float* __restrict__ s_x, int Kp)
+                                                                uint8_t* __restrict__ XL, float* __restrict__ s_x, int Kp, int Kz)
 {
+    // Kp: stored width of a lifted row (whole 128-byte units); Kz >= n_g * 2N + 8 / ES: elements
+    // of the quantised row held in LDS, those at and beyond K being zero (zero-completed last block)
     constexpr int ES = OUT >= 2 ? 2 : 1;                 // output element bytes
-    extern __shared__ uint32_t lds[];                     // K * ES bytes of quantised row + 8 bytes of slack (read, never used)
+    extern __shared__ uint32_t lds[];                     // Kz * ES bytes
     __shared__ float red[LQ_THREADS / 64];
     const int64_t m = blockIdx.x;
     const TIN* x = X + m * ldx;
@@ -134,69 +136,74 @@ __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __rest
             for (int k = t; k < K; k += LQ_THREADS) l16[k] = (uint16_t)quant1<OUT>(load_scalar(x + k), r);
         }
     }
+    if constexpr (ES == 1) {
+        uint8_t* l8 = reinterpret_cast<uint8_t*>(lds);
+        for (int k = K + t; k < Kz; k += LQ_THREADS) l8[k] = 0;
+    } else {
+        uint16_t* l16 = reinterpret_cast<uint16_t*>(lds);
+        for (int k = K + t; k < Kz; k += LQ_THREADS) l16[k] = 0;
+    }
     __syncthreads();
 
-    // ---- pass 2b: output-oriented gather of the lifted windows (window j reads b = 2N g + 2 l)
+    // ---- pass 2b: output-oriented gather of the lifted windows (window j reads b = 2N g + 2 l);
+    // windows at and beyond n_w = n_g (N-1) are the zero padding of the last 128-byte unit
     const int nw1 = N - 1;
     const int nwin = Kp / 4;
-    uint8_t* out = XL + m * (int64_t)Kp * ES;
+    const int ng = (K + 2 * N - 1) / (2 * N);
+    uint4* out = reinterpret_cast<uint4*>(XL + m * (int64_t)Kp * ES);
     if constexpr (ES == 1) {
-        if ((Kp & 15) == 0) {
-            for (int c = t; c < nwin / 4; c += LQ_THREADS) {
-                int j = 4 * c, g = j / nw1, l = j - g * nw1;
-                uint32_t w[4];
+        for (int c = t; c < nwin / 4; c += LQ_THREADS) {
+            int j = 4 * c, g = j / nw1, l = j - g * nw1;
+            uint32_t w[4];
 #pragma unroll
-                for (int i = 0; i < 4; ++i) {
+            for (int i = 0; i < 4; ++i) {
+                w[i] = 0;
+                if (g < ng) {
                     const int b = 2 * N * g + 2 * l;
                     const uint32_t lo = lds[b >> 2], hi = lds[(b >> 2) + 1];
                     w[i] = (b & 2) ? ((lo >> 16) | (hi << 16)) : lo;
-                    if (++l == nw1) { l = 0; ++g; }
                 }
-                reinterpret_cast<uint4*>(out)[c] = make_uint4(w[0], w[1], w[2], w[3]);
+                if (++l == nw1) { l = 0; ++g; }
             }
-        } else {
-            for (int j = t; j < nwin; j += LQ_THREADS) {
-                const int g = j / nw1, l = j - g * nw1, b = 2 * N * g + 2 * l;
-                const uint32_t lo = lds[b >> 2], hi = lds[(b >> 2) + 1];
-                reinterpret_cast<uint32_t*>(out)[j] = (b & 2) ? ((lo >> 16) | (hi << 16)) : lo;
-            }
+            out[c] = make_uint4(w[0], w[1], w[2], w[3]);
         }
     } else {
-        // bf16: a window is 8 bytes = elements b..b+3, b even -> two aligned dwords
-        if ((Kp & 7) == 0) {
-            for (int c = t; c < nwin / 2; c += LQ_THREADS) {
-                int j = 2 * c, g = j / nw1, l = j - g * nw1;
-                uint32_t w[4];
+        // 16-bit elements: a window is 8 bytes = elements b..b+3, b even -> two aligned dwords
+        for (int c = t; c < nwin / 2; c += LQ_THREADS) {
+            int j = 2 * c, g = j / nw1, l = j - g * nw1;
+            uint32_t w[4];
 #pragma unroll
-                for (int i = 0; i < 2; ++i) {
+            for (int i = 0; i < 2; ++i) {
+                w[2 * i] = 0; w[2 * i + 1] = 0;
+                if (g < ng) {
                     const int b = 2 * N * g + 2 * l;
                     w[2 * i] = lds[b >> 1]; w[2 * i + 1] = lds[(b >> 1) + 1];
-                    if (++l == nw1) { l = 0; ++g; }
                 }
-                reinterpret_cast<uint4*>(out)[c] = make_uint4(w[0], w[1], w[2], w[3]);
+                if (++l == nw1) { l = 0; ++g; }
             }
-        } else {
-            for (int j = t; j < nwin; j += LQ_THREADS) {
-                const int g = j / nw1, l = j - g * nw1, b = 2 * N * g + 2 * l;
-                reinterpret_cast<uint2*>(out)[j] = make_uint2(lds[b >> 1], lds[(b >> 1) + 1]);
-            }
+            out[c] = make_uint4(w[0], w[1], w[2], w[3]);
         }
     }
 }
+
+// elements of the quantised row kept in LDS: whole blocks plus 8 bytes that the gather may read
+// past the last window, rounded to whole dwords
+static inline int64_t lift_lds_elems(int64_t K, int N, int es) { return (n_groups(K, N) * 2 * N * es + 8 + 3) / 4 * 4 / es; }
 
 template <typename TIN, int OUT>
 static ss_status launch_lift(const void* X, int64_t M, int64_t K, int64_t ldx, int N, void* XL, float* s_x, hipStream_t st)
 {
     typedef InVec<TIN> IV;
-    const int Kp = (int)lifted_k(K, N);
     const int ES = OUT >= 2 ? 2 : 1;
-    const size_t lds_bytes = (size_t)K * ES + 8;
-    const bool vec_ok = (K % IV::N == 0) && (ldx % IV::N == 0) && (((uintptr_t)X & 15) == 0) && (((uintptr_t)XL & 15) == 0);
+    const int Kp = (int)lifted_ld(K, N, ES);
+    const int Kz = (int)lift_lds_elems(K, N, ES);
+    const size_t lds_bytes = (size_t)Kz * ES;
+    const bool vec_ok = (K % IV::N == 0) && (ldx % IV::N == 0) && (((uintptr_t)X & 15) == 0);
     const int64_t per_thread = (K / IV::N + LQ_THREADS - 1) / LQ_THREADS;
     dim3 grid((unsigned)M), block(LQ_THREADS);
     const TIN* x = static_cast<const TIN*>(X);
     uint8_t* xl = static_cast<uint8_t*>(XL);
-#define SS_LQ(MAXV) hipLaunchKernelGGL((k_act_lift_quant<TIN, OUT, MAXV>), grid, block, lds_bytes, st, x, ldx, (int)K, N, xl, s_x, Kp)
+#define SS_LQ(MAXV) hipLaunchKernelGGL((k_act_lift_quant<TIN, OUT, MAXV>), grid, block, lds_bytes, st, x, ldx, (int)K, N, xl, s_x, Kp, Kz)
     if (vec_ok && per_thread <= 4) SS_LQ(4);
     else if (vec_ok && per_thread <= 10) SS_LQ(10);
     else if (vec_ok && per_thread <= 20) SS_LQ(20);
@@ -227,11 +234,11 @@ __global__ __launch_bounds__(LQ_THREADS) void k_prune_quant(const TIN* __restric
         if (amax > 0.0f) { r = QMAX / amax; s = amax / QMAX; }
         if (t == 0) s_w[o] = s;
     }
-    const int L = 2 * N, ng = K / L;
+    const int L = 2 * N, ng = (K + L - 1) / L;            // a partial last block is completed with zeros
     for (int g = t; g < ng; g += LQ_THREADS) {
         float v[16];
 #pragma unroll
-        for (int k = 0; k < 16; ++k) v[k] = k < L ? load_scalar(w + g * L + k) : 0.0f;
+        for (int k = 0; k < 16; ++k) v[k] = (k < L && g * L + k < K) ? load_scalar(w + g * L + k) : 0.0f;
         // the two entries dropped are the last two in the order (|w| descending, index ascending)
         int d1 = 0, d2 = -1;
         float m1 = fabsf(v[0]);
@@ -242,7 +249,7 @@ __global__ __launch_bounds__(LQ_THREADS) void k_prune_quant(const TIN* __restric
         for (int k = 0; k < 16; ++k) if (k < L && k != d1 && (d2 < 0 || fabsf(v[k]) <= m2)) { m2 = fabsf(v[k]); d2 = k; }
 #pragma unroll
         for (int k = 0; k < 16; ++k) {
-            if (k < L) {
+            if (k < L && g * L + k < K) {
                 const uint32_t q = (k == d1 || k == d2) ? 0u : quant1<OUT>(v[k], r);
                 if constexpr (ES == 1) Wq[o * (int64_t)K + g * L + k] = (uint8_t)q;
                 else reinterpret_cast<uint16_t*>(Wq)[o * (int64_t)K + g * L + k] = (uint16_t)q;
@@ -257,20 +264,27 @@ using namespace ss;
 
 extern "C" int64_t slide_lifted_k(int64_t K, int N)
 {
-    if (!valid_N(N) || K <= 0 || K % (2 * N) != 0) return -1;
+    if (!valid_N(N) || K <= 0 || K > (1 << 24)) return -1;
     return lifted_k(K, N);
+}
+
+extern "C" int64_t slide_lifted_ld(int64_t K, int N, ss_dtype dtype)
+{
+    if (!valid_N(N) || K <= 0 || K > (1 << 24) || !valid_dtype(dtype)) return -1;
+    return lifted_ld(K, N, elem_size(dtype));
 }
 
 extern "C" ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_t K, int64_t ldx, int N,
                                     ss_dtype out, void* X_lifted, float* s_x, void* stream)
 {
     if (!valid_N(N)) return SS_ERR_BAD_PATTERN_N;
-    if (M < 0 || K <= 0 || K % (2 * N) != 0 || ldx < K || K > (1 << 24) || M > 0x7FFFFFFF) return SS_ERR_SHAPE;
+    if (M < 0 || K <= 0 || ldx < K || K > (1 << 24) || M > 0x7FFFFFFF) return SS_ERR_SHAPE;
     if (in_dtype != SS_IN_F32 && in_dtype != SS_IN_BF16) return SS_ERR_DTYPE;
     if (!valid_dtype(out)) return SS_ERR_DTYPE;
-    if ((size_t)K * elem_size(out) + 8 > 64 * 1024) return SS_ERR_SHAPE;    // quantised row must fit in LDS
+    if ((size_t)lift_lds_elems(K, N, elem_size(out)) * elem_size(out) > 64 * 1024) return SS_ERR_SHAPE;    // quantised row must fit in LDS
     if (M == 0) return SS_OK;
     if (!X || !X_lifted || (!unscaled(out) && !s_x)) return SS_ERR_NULL;
+    if ((uintptr_t)X_lifted & 15) return SS_ERR_SHAPE;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (in_dtype == SS_IN_F32) {
         if (out == SS_I8) return launch_lift<float, 0>(X, M, K, ldx, N, X_lifted, s_x, st);
@@ -296,7 +310,7 @@ extern "C" ss_status slide_prune_quant(const void* W, ss_act_dtype in_dtype, int
                                        void* Wq, float* s_w, void* stream)
 {
     if (!valid_N(N)) return SS_ERR_BAD_PATTERN_N;
-    if (O < 0 || K <= 0 || K % (2 * N) != 0 || K > (1 << 24) || O > 0x7FFFFFFF) return SS_ERR_SHAPE;
+    if (O < 0 || K <= 0 || K > (1 << 24) || O > 0x7FFFFFFF) return SS_ERR_SHAPE;
     if (in_dtype != SS_IN_F32 && in_dtype != SS_IN_BF16) return SS_ERR_DTYPE;
     if (!valid_dtype(dtype)) return SS_ERR_DTYPE;
     if (O == 0) return SS_OK;

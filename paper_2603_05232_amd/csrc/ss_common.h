@@ -25,7 +25,12 @@ constexpr int PANEL = 128;
 // K' granularity of the packed format and of both GEMMs.
 constexpr int KSTEP = 128;
 
-__host__ __device__ inline int64_t lifted_k(int64_t K, int N) { return (K / (2 * N)) * 4 * (N - 1); }
+// Alg. 1: n_g = ceil(K / 2N) blocks (the last one completed with zeros), K' = 4 n_g (N-1).
+__host__ __device__ inline int64_t n_groups(int64_t K, int N) { return (K + 2 * N - 1) / (2 * N); }
+__host__ __device__ inline int64_t lifted_k(int64_t K, int N) { return n_groups(K, N) * 4 * (N - 1); }
+// Stored width (elements of es bytes) of a lifted row: K' rounded up to whole 128-byte k units;
+// the columns beyond K' hold zeros (activations) / all-zero windows (weights).
+inline int64_t lifted_ld(int64_t K, int N, int es) { const int64_t per = KSTEP / es; return (lifted_k(K, N) + per - 1) / per * per; }
 inline bool valid_N(int N) { return N >= 2 && N <= 8; }
 inline int elem_size(ss_dtype d) { return (d == SS_BF16 || d == SS_FP16) ? 2 : 1; }
 inline bool valid_dtype(ss_dtype d) { return d == SS_I8 || d == SS_FP8_E4M3 || d == SS_BF16 || d == SS_FP16; }

@@ -35,9 +35,22 @@ def test_lifted_k(lib):
     assert binding.slide_lifted_k(6144, 3) == 8192
     assert binding.slide_lifted_k(5120, 5) == 8192
     assert binding.slide_lifted_k(64, 2) == 64
-    assert binding.slide_lifted_k(100, 4) == -1
+    assert binding.slide_lifted_k(100, 4) == 13 * 12         # ceil(100 / 8) blocks (Alg. 1's n_g)
+    assert binding.slide_lifted_k(3584, 3) == 598 * 8
+    assert binding.slide_lifted_k((1 << 24) + 1, 4) == -1
     assert binding.slide_lifted_k(64, 1) == -1 and binding.slide_lifted_k(64, 9) == -1
     assert binding.slide_lifted_k(0, 4) == -1
+
+
+def test_lifted_ld(lib):
+    # stored width: K' rounded up to whole 128-byte units
+    assert binding.slide_lifted_ld(512, 4, "i8") == 768 and binding.slide_lifted_ld(3584, 4, "i8") == 5376
+    assert binding.slide_lifted_ld(100, 4, "i8") == 256 and binding.slide_lifted_ld(100, 4, "bf16") == 192
+    assert binding.slide_lifted_ld(3584, 3, "fp8") == 4864     # K' = 4784
+    assert binding.slide_lifted_ld(6912, 4, "i8") == 10368 and binding.slide_lifted_ld(6912, 5, "i8") == 11136   # K' = 11072 = 86.5 units
+    assert binding.slide_lifted_ld(1, 2, "fp16") == 64
+    assert binding.slide_lifted_ld(64, 9, "i8") == -1 and binding.slide_lifted_ld(0, 4, "i8") == -1
+    assert binding.load().slide_lifted_ld(64, 4, 7) == -1
 
 
 def test_packed_sizes(lib):
@@ -52,9 +65,8 @@ def test_packed_sizes(lib):
     assert (v, m) == (512 * 384 * 2, 512 * 96 * 2)
     assert binding.slide_packed_sizes(128, 128, 4, "bf16")[0] == 128 * 96 * 2   # K' = 192: 384 lifted bytes per row
     assert binding.slide_packed_sizes(512, 512, 4, "fp16") == (v, m)
-    with pytest.raises(binding.SlideSparseError) as e:
-        binding.slide_packed_sizes(512, 520, 4, "i8")       # K' = 780 is not a multiple of 128
-    assert e.value.code == 3
+    assert binding.slide_packed_sizes(512, 520, 4, "i8") == (512 * 448, 512 * 112)   # K' = 780 stored as 896
+    assert binding.slide_packed_sizes(128, 100, 4, "i8") == (128 * 128, 128 * 32)    # partial last block
 
 
 def test_argument_errors_return_codes(lib):
@@ -63,9 +75,10 @@ def test_argument_errors_return_codes(lib):
     # bad N
     assert lib.act_lift_quant(one, 0, 4, 64, 64, 1, 0, one, one, None) == 2
     assert lib.slide_decompose(one, 4, 64, 9, 0, one, one, None, None) == 2
-    # K not a multiple of 2N, ldx < K
-    assert lib.act_lift_quant(one, 0, 4, 60, 60, 4, 0, one, one, None) == 3
+    # ldx < K, output not 16-byte aligned, row too long for on-chip staging
     assert lib.act_lift_quant(one, 0, 4, 64, 32, 4, 0, one, one, None) == 3
+    assert lib.act_lift_quant(one, 0, 4, 64, 64, 4, 0, ctypes.c_void_p(8), one, None) == 3
+    assert lib.act_lift_quant(one, 0, 4, 65536, 65536, 4, 0, one, one, None) == 3
     # bad dtypes
     assert lib.act_lift_quant(one, 7, 4, 64, 64, 4, 0, one, one, None) == 4
     assert lib.act_lift_quant(one, 0, 4, 64, 64, 4, 5, one, one, None) == 4

@@ -40,10 +40,24 @@ def from_dev_q(t, dtype):
     return host(t)
 
 
+def check_lifted(got, exp, dtype):
+    """X_lifted rows are stored K' rounded up to whole 128-byte units wide: the first K' columns
+    are the oracle's lifted row, the rest is zero padding."""
+    got = from_dev_q(got, dtype)
+    per = 128 // got.dtype.itemsize
+    Kp = exp.shape[1]
+    assert got.shape == (exp.shape[0], (Kp + per - 1) // per * per)
+    assert np.array_equal(got[:, :Kp], exp)
+    assert not got[:, Kp:].any()
+
+
 # ------------------------------------------------------------------ act_lift_quant
 @pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("N,M,K", [(4, 16, 512), (2, 7, 64), (3, 5, 6 * 37), (4, 33, 3584), (5, 3, 5120), (8, 4, 16 * 9),
-                                   (4, 2, 18944), (3, 9, 6144), (4, 3, 8 * 3001)])
+                                   (4, 2, 18944), (3, 9, 6144), (4, 3, 8 * 3001),
+                                   # K not a multiple of 2N: the last block is completed with zeros (Alg. 1, n_g = ceil(K / 2N))
+                                   (3, 5, 100), (4, 7, 3001), (5, 3, 6912), (2, 4, 63), (8, 3, 17), (4, 2, 1), (3, 6, 3584),
+                                   (7, 3, 4099)])
 def test_act_lift_quant_fp32(dtype, N, M, K):
     X = synth.activations(M, K, seed=N * 100 + M, n_outliers=min(4, K // 8))
     if M > 2:
@@ -51,8 +65,7 @@ def test_act_lift_quant_fp32(dtype, N, M, K):
         X[2, K // 2] = -3.0 * np.abs(X[2]).max()              # negative extreme
     exp, s = so.act_lift_quant(X, N, dtype)
     got, gs = binding.act_lift_quant(dev(X), N, dtype)
-    assert tuple(got.shape) == exp.shape
-    assert np.array_equal(from_dev_q(got, dtype), exp)
+    check_lifted(got, exp, dtype)
     if dtype in ("bf16", "fp16"):
         assert gs is None
     else:
@@ -67,7 +80,7 @@ def test_act_lift_quant_bf16_input_and_row_stride(dtype):
     exp, s = so.act_lift_quant(so.bf16_to_f32(Xb), N, dtype)
     xt = dev(Xb.view(np.int16)).view(torch.bfloat16)
     got, gs = binding.act_lift_quant(xt, N, dtype)
-    assert np.array_equal(from_dev_q(got, dtype), exp)
+    check_lifted(got, exp, dtype)
     if dtype not in ("bf16", "fp16"):
         assert np.array_equal(host(gs), s)
     # strided rows (a column slice of a wider matrix), fp32
@@ -75,15 +88,23 @@ def test_act_lift_quant_bf16_input_and_row_stride(dtype):
     wide[:, 32:32 + K] = Xf
     exp2, s2 = so.act_lift_quant(Xf, N, dtype)
     got2, gs2 = binding.act_lift_quant(dev(wide)[:, 32:32 + K], N, dtype)
-    assert np.array_equal(from_dev_q(got2, dtype), exp2)
+    check_lifted(got2, exp2, dtype)
+    # bf16 input whose length is neither a multiple of 2N nor of the vector width
+    K3 = 1003
+    exp3, s3 = so.act_lift_quant(so.bf16_to_f32(Xb[:, :K3]), N, dtype)
+    got3, gs3 = binding.act_lift_quant(xt[:, :K3], N, dtype)
+    check_lifted(got3, exp3, dtype)
+    if dtype not in ("bf16", "fp16"):
+        assert np.array_equal(host(gs3), s3)
 
 
 # ------------------------------------------------------------------ slide_prune_quant
 @pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
-@pytest.mark.parametrize("N,O,K", [(4, 512, 512), (2, 9, 64), (3, 17, 6 * 50), (5, 6, 5120), (8, 5, 16 * 11)])
+@pytest.mark.parametrize("N,O,K", [(4, 512, 512), (2, 9, 64), (3, 17, 6 * 50), (5, 6, 5120), (8, 5, 16 * 11),
+                                   (3, 17, 100), (4, 9, 3001), (4, 5, 7), (8, 6, 15 + 32), (2, 3, 5), (5, 4, 6912)])
 def test_prune_quant(dtype, N, O, K):
     W = synth.weights(O, K, seed=N)
-    W[0, : 2 * N] = 0.5                                       # ties: the lower indices survive
+    W[0, : min(K, 2 * N)] = 0.5                               # ties: the lower indices survive
     if O > 3:
         W[3] = 0.0
     expq, exps = so.prepare_weights(W, N, dtype)
@@ -95,7 +116,8 @@ def test_prune_quant(dtype, N, O, K):
 
 # ------------------------------------------------------------------ slide_decompose (canonical form)
 @pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
-@pytest.mark.parametrize("N,O,K", [(4, 512, 512), (2, 5, 64), (3, 33, 6 * 21), (5, 7, 200), (6, 3, 120), (7, 2, 14 * 5), (8, 4, 160)])
+@pytest.mark.parametrize("N,O,K", [(4, 512, 512), (2, 5, 64), (3, 33, 6 * 21), (5, 7, 200), (6, 3, 120), (7, 2, 14 * 5), (8, 4, 160),
+                                   (3, 9, 100), (4, 5, 3001), (8, 3, 17), (2, 4, 63), (5, 2, 1), (6, 7, 131)])
 def test_decompose_canonical(dtype, N, O, K):
     W = synth.weights(O, K, seed=10 + N)
     Wq, _ = so.prepare_weights(W, N, dtype)
@@ -293,7 +315,21 @@ def _random_cases(n, seed):
     return cases
 
 
-@pytest.mark.parametrize("N,M,O,K", _random_cases(24, seed=2024))
+def _ragged_k_cases(n, seed):
+    """K neither a multiple of 2N nor of the 128-byte unit (last block completed with zeros, Alg. 1's
+    n_g = ceil(K / 2N); lifted rows padded to whole units), plus two layer shapes of that kind."""
+    rng = np.random.default_rng(seed)
+    cases = [(3, 64, 96, 3584), (5, 130, 160, 6912)]        # 4:6 on a 3584-wide layer, 8:10 on a 6912-wide one
+    for _ in range(n):
+        N = int(rng.integers(2, 9))
+        K = int(rng.integers(2, 1500))
+        M = int(rng.choice([1, 17, 64, 65, 128, 129, 300]))
+        O = int(rng.choice([1, 33, 128, 257, 513]))
+        cases.append((N, M, O, K))
+    return cases
+
+
+@pytest.mark.parametrize("N,M,O,K", _random_cases(24, seed=2024) + _ragged_k_cases(14, seed=31))
 def test_random_shapes_int8_end_to_end(N, M, O, K):
     """The whole path on ragged shapes around every tile, fragment and token-block boundary, for every
     pattern N = 2..8: prune + quantise, decompose, lift + quantise, sparse GEMM, dense GEMM; all bit-exact."""
@@ -305,17 +341,19 @@ def test_random_shapes_int8_end_to_end(N, M, O, K):
     assert np.array_equal(host(Wq), ref["Wq"]) and np.array_equal(host(s_w), ref["s_w"])
     w_vals, w_meta, viol = binding.slide_decompose(Wq, N, "i8", count_violations=True)
     XL, s_x = binding.act_lift_quant(Xd, N, "i8")
-    assert np.array_equal(host(XL), so.lift(ref["Xq"], N)) and np.array_equal(host(s_x), ref["s_x"])
+    check_lifted(XL, so.lift(ref["Xq"], N), "i8")
+    assert np.array_equal(host(s_x), ref["s_x"])
     Y = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, "i8")
     assert int(host(viol)[0]) == 0
     assert np.array_equal(bits16(Y), ref["Y"])
-    Xq, s_x2 = binding.act_lift_quant(Xd, 2, "i8")
-    Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, "i8")
-    assert np.array_equal(bits16(Yd), ref["Y"])
+    if K % 128 == 0:                                         # the dense baseline wants whole 128-byte rows
+        Xq, s_x2 = binding.act_lift_quant(Xd, 2, "i8")
+        Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, "i8")
+        assert np.array_equal(bits16(Yd), ref["Y"])
 
 
 @pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
-@pytest.mark.parametrize("N,M,O,K", _random_cases(8, seed=77))
+@pytest.mark.parametrize("N,M,O,K", _random_cases(8, seed=77) + _ragged_k_cases(6, seed=32))
 def test_random_shapes_float_end_to_end(dtype, N, M, O, K):
     X = synth.activations(M, K, seed=M + O + K, n_outliers=2)
     W = synth.weights(O, K, seed=M + O + N)
@@ -325,7 +363,8 @@ def test_random_shapes_float_end_to_end(dtype, N, M, O, K):
     assert np.array_equal(from_dev_q(Wq, dtype), ref["Wq"])
     w_vals, w_meta = binding.slide_decompose(Wq, N, dtype)
     XL, s_x = binding.act_lift_quant(Xd, N, dtype)
-    assert np.array_equal(from_dev_q(XL, dtype), so.lift(ref["Xq"], N))
+    check_lifted(XL, so.lift(ref["Xq"], N), dtype)
     _float_gemm_check(bits16(binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype)), ref, dtype)
-    Xq, s_x2 = binding.act_lift_quant(Xd, 2, dtype)
-    _float_gemm_check(bits16(binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype)), ref, dtype)
+    if K * XL.element_size() % 128 == 0:
+        Xq, s_x2 = binding.act_lift_quant(Xd, 2, dtype)
+        _float_gemm_check(bits16(binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype)), ref, dtype)
