@@ -49,10 +49,10 @@ def parse():
     ap.add_argument("--vendor-baseline", action="store_true",
                     help="context only: also time torch._int_mm (the vendor library's INT8 GEMM, int32 output, no scale epilogue) on "
                          "the four layer shapes")
-    ap.add_argument("--sweep", choices=["dtypes_m", "patterns", "llama_block"], default=None,
+    ap.add_argument("--sweep", choices=["dtypes_m", "mid_m", "patterns", "llama_block"], default=None,
                     help="instead of the headline step, time one of the other benchmark configurations and print its table "
                          "as one JSON line: dtypes_m = INT8/FP8/BF16 at M in {1,16,128,8192} on the Qwen2.5-7B shapes; "
-                         "patterns = 4:6, 6:8, 8:10 at M=8192 INT8; llama_block = Llama-3-8B linears at M=4096, 6:8 INT8")
+                         "mid_m = INT8 at M in {64..2048}; patterns = 4:6, 6:8, 8:10 at M=8192 INT8; llama_block = Llama-3-8B linears at M=4096, 6:8 INT8")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--cpu-sample-channels", type=int, default=8192)
     return ap.parse_args()
@@ -92,6 +92,8 @@ def sweep(args, torch, binding, synth, dev):
     """Times lift + sparse GEMM against quantise + dense GEMM for every case of one configuration."""
     if args.sweep == "dtypes_m":
         cases = [(dt, M, 4, name, K, O) for dt in ("i8", "fp8", "bf16") for M in (1, 16, 128, 8192) for name, K, O in synth.QWEN25_7B]
+    elif args.sweep == "mid_m":
+        cases = [("i8", M, 4, name, K, O) for M in (64, 128, 256, 512, 1024, 2048) for name, K, O in synth.QWEN25_7B]
     elif args.sweep == "patterns":
         cases = [("i8", 8192, N, f"{2 * N - 2}:{2 * N}", K, O) for N, K, O in synth.PATTERN_SWEEP]
     else:
@@ -109,10 +111,13 @@ def sweep(args, torch, binding, synth, dev):
         XL, s_x = binding.act_lift_quant(X, N, dt)
         Xq, s_xd = binding.act_lift_quant(X, 2, dt)
         Y = torch.empty((M, O), dtype=torch.bfloat16, device=dev)
+        # scratch for the shapes whose k range is split over workgroups (0 bytes where it is not)
+        ws_bytes = (binding.slide_gemm_workspace_bytes(M, O, XL.shape[1], dt), binding.slide_gemm_workspace_bytes(M, O, K, dt))
+        ws_s, ws_d = (torch.empty((n,), dtype=torch.uint8, device=dev) if n else None for n in ws_bytes)
         fns = {"lift": lambda: binding.act_lift_quant(X, N, dt, out=XL, s_x=s_x),
-               "sparse": lambda: binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dt, out=Y),
+               "sparse": lambda: binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dt, out=Y, workspace=ws_s),
                "quant": lambda: binding.act_lift_quant(X, 2, dt, out=Xq, s_x=s_xd),
-               "dense": lambda: binding.dense_gemm(Xq, s_xd, Wq, s_w, dt, out=Y)}
+               "dense": lambda: binding.dense_gemm(Xq, s_xd, Wq, s_w, dt, out=Y, workspace=ws_d)}
         t = {}
         for k, fn in fns.items():
             for _ in range(args.warmup):
@@ -131,7 +136,8 @@ def sweep(args, torch, binding, synth, dev):
                      "gemm_speedup": t["dense"] / t["sparse"], "layer_speedup": (t["quant"] + t["dense"]) / (t["lift"] + t["sparse"]),
                      "sparse_frac_of_sparse_peak": 2.0 * M * O * Kp / (t["sparse"] * 1e-3) * 1e-12 / (2 * peak[dt]),
                      "dense_frac_of_dense_peak": 2.0 * M * O * K / (t["dense"] * 1e-3) * 1e-12 / peak[dt],
-                     "sparse_gemm_algorithmic_GBps": sparse_bytes / (t["sparse"] * 1e-3) * 1e-9})
+                     "sparse_gemm_algorithmic_GBps": sparse_bytes / (t["sparse"] * 1e-3) * 1e-9,
+                     "workspace_MiB": [ws_bytes[0] / 2 ** 20, ws_bytes[1] / 2 ** 20]})
         del X, Wq, w_vals, w_meta, XL, Xq, Y
     print(json.dumps({"sweep": args.sweep, "steps": args.steps, "warmup": args.warmup, "speedup_bound": "N/(N-1)", "cases": rows}))
 

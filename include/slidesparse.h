@@ -17,7 +17,8 @@
  *
  * Conventions for every call
  *   - every data pointer is a DEVICE pointer owned by the caller; the library never
- *     allocates, frees or keeps a pointer after the call returns;
+ *     allocates, frees or keeps a pointer after the call returns (scratch memory, where a
+ *     call can use it, is passed in by the caller);
  *   - work is enqueued on `stream` (a hipStream_t passed as void*; NULL = default
  *     stream) and the call returns without synchronising;
  *   - arguments are validated on the host before anything is enqueued; a bad argument
@@ -42,7 +43,7 @@ typedef enum {
     SS_ERR_BAD_PATTERN_N = 2,  /* N outside 2..8                                              */
     SS_ERR_SHAPE = 3,          /* a size is non-positive or violates a divisibility rule      */
     SS_ERR_DTYPE = 4,          /* unknown or unsupported dtype for this call                  */
-    SS_ERR_WORKSPACE = 5,      /* reserved                                                    */
+    SS_ERR_WORKSPACE = 5,      /* workspace pointer not 16-byte aligned                       */
     SS_ERR_HIP = 6             /* the HIP runtime reported an error at launch                 */
 } ss_status;
 
@@ -125,8 +126,10 @@ ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_
  * for the same O, K and N.  Y is bf16 [M,O] with row stride ldy (elements, O <= ldy < 2^22).  INT8 accumulates
  * in int32 (exact), FP8 and BF16 in fp32 in the order of the matrix instructions.
  * Requires K_lifted * sizeof(element) % 128 == 0 (and <= 2^23 bytes per row), M <= 2^24, and 16-byte
- * aligned operand pointers.  For M <= 64 (or M <= 128 with O < 16384) kernels that stream the weights once
- * are used instead of the 256 x 256 tile kernels; results are the same (INT8) or within rounding order. */
+ * aligned operand pointers.  Three kernel families are chosen from M, O and K_lifted: kernels that
+ * stream the weights once (few tokens), 128 x 128 tiles (shapes too small to fill the chip with
+ * large tiles) and persistent 256 x 256 tiles; results are the same (INT8) or differ in fp32
+ * summation order only.  Every call with the same arguments gives the same bits. */
 ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, const void* w_vals,
                             const void* w_meta, const float* s_w, int64_t M, int64_t O,
                             int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy, void* stream);
@@ -137,6 +140,25 @@ ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, const void* 
 ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq, const float* s_w,
                      int64_t M, int64_t O, int64_t K, ss_dtype dtype, void* Y, int64_t ldy,
                      void* stream);
+
+/* The same two GEMMs with a caller-owned scratch buffer (Sec. 5 measures from decode, M = 64, to
+ * prefill; small M leaves most of the chip idle unless the k range is split).  With a workspace of
+ * at least slide_gemm_workspace_bytes() the 128 x 128-tile kernels split the k range of a tile
+ * over several workgroups, write fp32 / int32 partial sums to the workspace and add them in a
+ * fixed order in a second kernel (bit-reproducible; INT8 results are identical to the calls
+ * without workspace).  workspace: device memory, 16-byte aligned (SS_ERR_WORKSPACE otherwise),
+ * contents irrelevant before and undefined after; NULL with workspace_bytes = 0, or a smaller
+ * buffer, is allowed and gives fewer or no splits.  Calls that share one workspace must be ordered
+ * on one stream.  K is the row length in elements as passed to the GEMM (K_lifted for the sparse
+ * one); the function returns 0 when the shape would not be split or an argument is invalid. */
+size_t slide_gemm_workspace_bytes(int64_t M, int64_t O, int64_t K, ss_dtype dtype);
+ss_status slide_sparse_gemm_ws(const void* X_lifted, const float* s_x, const void* w_vals,
+                               const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                               int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy,
+                               void* workspace, size_t workspace_bytes, void* stream);
+ss_status dense_gemm_ws(const void* Xq, const float* s_x, const void* Wq, const float* s_w,
+                        int64_t M, int64_t O, int64_t K, ss_dtype dtype, void* Y, int64_t ldy,
+                        void* workspace, size_t workspace_bytes, void* stream);
 
 const char* ss_status_string(ss_status s);
 

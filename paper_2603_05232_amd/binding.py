@@ -19,6 +19,7 @@ SS_IN_F32, SS_IN_BF16 = 0, 1
 DTYPE_CODE = {"i8": SS_I8, "fp8": SS_FP8_E4M3, "bf16": SS_BF16, "fp16": SS_FP16}
 EXPORTS = ("slide_lifted_k", "slide_lifted_ld", "slide_packed_sizes", "slide_prune_quant", "slide_decompose",
            "slide_decompose_canonical", "act_lift_quant", "slide_sparse_gemm", "dense_gemm",
+           "slide_gemm_workspace_bytes", "slide_sparse_gemm_ws", "dense_gemm_ws",
            "ss_status_string", "slide_format_version")
 
 _lib = None
@@ -50,8 +51,12 @@ def load():
     lib.act_lift_quant.argtypes = [vp, i32, i64, i64, i64, i32, i32, vp, vp, vp]
     lib.slide_sparse_gemm.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, i64, vp]
     lib.dense_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, i64, vp]
+    lib.slide_sparse_gemm_ws.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, i64, vp, sz, vp]
+    lib.dense_gemm_ws.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, i64, vp, sz, vp]
+    lib.slide_gemm_workspace_bytes.argtypes = [i64, i64, i64, i32]
+    lib.slide_gemm_workspace_bytes.restype = sz
     for name in ("slide_packed_sizes", "slide_prune_quant", "slide_decompose", "slide_decompose_canonical",
-                 "act_lift_quant", "slide_sparse_gemm", "dense_gemm"):
+                 "act_lift_quant", "slide_sparse_gemm", "dense_gemm", "slide_sparse_gemm_ws", "dense_gemm_ws"):
         getattr(lib, name).restype = i32
     lib.ss_status_string.argtypes = [i32]
     lib.ss_status_string.restype = ctypes.c_char_p
@@ -159,24 +164,38 @@ def act_lift_quant(X: torch.Tensor, N: int, dtype: str, out=None, s_x=None):
     return out, s_x
 
 
-def slide_sparse_gemm(X_lifted, s_x, w_vals, w_meta, s_w, O: int, dtype: str, out=None):
-    """Y[M,O] bf16 = epilogue(X_lifted[M,Kld] . W'^T)."""
+def slide_gemm_workspace_bytes(M: int, O: int, K: int, dtype: str) -> int:
+    return int(load().slide_gemm_workspace_bytes(M, O, K, DTYPE_CODE[dtype]))
+
+
+def slide_sparse_gemm(X_lifted, s_x, w_vals, w_meta, s_w, O: int, dtype: str, out=None, workspace=None):
+    """Y[M,O] bf16 = epilogue(X_lifted[M,Kld] . W'^T); workspace: optional uint8 device tensor (slide_sparse_gemm_ws)."""
     M, Kp = X_lifted.shape
     assert X_lifted.is_contiguous()
     if out is None:
         out = torch.empty((M, O), dtype=torch.bfloat16, device=X_lifted.device)
-    _check(load().slide_sparse_gemm(_ptr(X_lifted), _ptr(s_x), _ptr(w_vals), _ptr(w_meta), _ptr(s_w), M, O, Kp,
-                                    DTYPE_CODE[dtype], _ptr(out), out.stride(0), _stream()), "slide_sparse_gemm")
+    if workspace is None:
+        _check(load().slide_sparse_gemm(_ptr(X_lifted), _ptr(s_x), _ptr(w_vals), _ptr(w_meta), _ptr(s_w), M, O, Kp,
+                                        DTYPE_CODE[dtype], _ptr(out), out.stride(0), _stream()), "slide_sparse_gemm")
+    else:
+        _check(load().slide_sparse_gemm_ws(_ptr(X_lifted), _ptr(s_x), _ptr(w_vals), _ptr(w_meta), _ptr(s_w), M, O, Kp,
+                                           DTYPE_CODE[dtype], _ptr(out), out.stride(0), _ptr(workspace),
+                                           workspace.numel() * workspace.element_size(), _stream()), "slide_sparse_gemm_ws")
     return out
 
 
-def dense_gemm(Xq, s_x, Wq, s_w, dtype: str, out=None):
-    """Y[M,O] bf16 = epilogue(Xq[M,K] . Wq[O,K]^T)."""
+def dense_gemm(Xq, s_x, Wq, s_w, dtype: str, out=None, workspace=None):
+    """Y[M,O] bf16 = epilogue(Xq[M,K] . Wq[O,K]^T); workspace: optional uint8 device tensor (dense_gemm_ws)."""
     M, K = Xq.shape
     O = Wq.shape[0]
     assert Xq.is_contiguous() and Wq.is_contiguous() and Wq.shape[1] == K
     if out is None:
         out = torch.empty((M, O), dtype=torch.bfloat16, device=Xq.device)
-    _check(load().dense_gemm(_ptr(Xq), _ptr(s_x), _ptr(Wq), _ptr(s_w), M, O, K, DTYPE_CODE[dtype], _ptr(out),
-                             out.stride(0), _stream()), "dense_gemm")
+    if workspace is None:
+        _check(load().dense_gemm(_ptr(Xq), _ptr(s_x), _ptr(Wq), _ptr(s_w), M, O, K, DTYPE_CODE[dtype], _ptr(out),
+                                 out.stride(0), _stream()), "dense_gemm")
+    else:
+        _check(load().dense_gemm_ws(_ptr(Xq), _ptr(s_x), _ptr(Wq), _ptr(s_w), M, O, K, DTYPE_CODE[dtype], _ptr(out),
+                                    out.stride(0), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
+               "dense_gemm_ws")
     return out

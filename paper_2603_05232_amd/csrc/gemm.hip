@@ -29,6 +29,7 @@
 #include "ss_common.h"
 #include "packed_layout.h"
 #include "mma_types.h"
+#include "lds_pipe.h"
 #include <type_traits>
 
 
@@ -39,62 +40,6 @@ constexpr int G_THREADS = 64 * G_WAVES;
 constexpr int NBF = 2;    // 32-token B fragments per wavefront (4 x 2 accumulator blocks of 32 x 32)
 constexpr int BO = 256;   // output channels per workgroup
 constexpr int BT = 256;   // tokens per workgroup
-constexpr int ROWB = 128; // bytes of one LDS row of a row-major operand tile (one cache line)
-
-typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void gbl_void;
-
-// 16 (or 4) bytes per lane, global -> LDS; the LDS address is wave-uniform base + lane * size.  The global
-// address is given as a wave-uniform pointer plus a 32-bit lane offset; the empty asm pins the uniform part
-// in scalar registers so that the load uses its scalar-base addressing form and the lane part stays one
-// 32-bit register (otherwise the compiler keeps a 64-bit per-lane address alive for every load stream).
-__device__ inline void lds_dma16(const uint8_t* uniform_base, uint32_t lane_off, void* lds_wave_base)
-{
-    asm volatile("" : "+s"(uniform_base));
-    __builtin_amdgcn_global_load_lds((gbl_void*)(uniform_base + lane_off), (lds_void*)lds_wave_base, 16, 0, 0);
-}
-__device__ inline void lds_dma4(const uint8_t* uniform_base, uint32_t lane_off, void* lds_wave_base)
-{
-    asm volatile("" : "+s"(uniform_base));
-    __builtin_amdgcn_global_load_lds((gbl_void*)(uniform_base + lane_off), (lds_void*)lds_wave_base, 4, 0, 0);
-}
-
-// Lane id read from the hardware.  Code that runs once per tile (loader set-up, epilogue) takes the lane id from
-// here instead of keeping threadIdx-derived values alive through the k loop, where every register is taken:
-// what the compiler cannot keep it spills, and a spill reload waits for all direct loads in flight.
-__device__ inline int fresh_lane()
-{
-    int l;
-    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(l));
-    return l;
-}
-
-// Wait until at most N of this wave's direct loads are still in flight and all of its LDS reads
-// have returned (gfx9 s_waitcnt encoding: vmcnt = bits [3:0] and [15:14], lgkmcnt = bits [11:8]).
-template <int N> __device__ inline void wait_vmcnt()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
-    asm volatile("" ::: "memory");
-}
-
-// all LDS reads of this wave have returned (loads in flight are left alone)
-__device__ inline void wait_lgkm0()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_waitcnt(0xF | (0x3 << 14) | (0x7 << 4) | (0x0 << 8));
-    asm volatile("" ::: "memory");
-}
-
-// Workgroup barrier without the memory fence of __syncthreads(): direct-to-LDS loads in flight
-// for later units must stay in flight.  The empty asm statements keep the compiler from moving
-// LDS accesses or load issues across it.
-__device__ inline void wg_barrier()
-{
-    asm volatile("" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    asm volatile("" ::: "memory");
-}
 
 // Persistent workgroups: the grid holds one workgroup per compute unit and workgroup b processes
 // tiles b, b + grid, b + 2 grid, ...  Workgroup ids go round-robin to the 8 XCDs, so within a full
@@ -117,7 +62,6 @@ __device__ inline bool tile_of_round(int round, int tiles_o, int tiles_t, int& t
 }
 
 // ---- LDS tile of a row-major 8-bit operand: 256 rows x 128 bytes, XOR-swizzled -----------------
-__device__ inline int swz(int row) { return (row >> 1) & 7; }
 
 // per-thread source pointers (k offset 0) of the direct loads that fill a [256 x 128 B] tile; rows
 // beyond nrows are clamped (their products are never stored)
@@ -149,11 +93,6 @@ struct RowTileLoader {
         for (int i = 0; i < ROW_LOADS; ++i) issue_one(i, k0, lds_tile, wave);
     }
 };
-
-__device__ inline const v4i* tile_chunk(const uint8_t* lds_tile, int row, int lc)
-{
-    return reinterpret_cast<const v4i*>(lds_tile + row * ROWB + ((lc ^ swz(row)) << 4));
-}
 
 // ---- epilogue: Y = bf16((float(acc) * s_x) * s_w), staged through LDS for coalesced stores ------
 
@@ -639,18 +578,15 @@ static ss_status launch_sparse(const void* XL, const float* s_x, const void* w_v
     return launch_status();
 }
 
-extern "C" ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t K,
-                                ss_dtype dtype, void* Y, int64_t ldy, void* stream)
+// 256 x 256 tile kernels (arguments already validated)
+namespace ss {
+
+ss_status launch_dense_tile(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, ss_dtype dtype,
+                            void* Y, int64_t ldy, hipStream_t hs)
 {
-    ss_status st = check_gemm(Xq, s_x, Wq, s_w, M, O, K, dtype, Y, ldy);
-    if (st != SS_OK || M == 0 || O == 0) return st;
-    if (use_skinny(M, O))
-        return launch_dense_skinny(Xq, s_x, Wq, s_w, M, O, K * elem_size(dtype), dtype, Y, ldy, static_cast<hipStream_t>(stream));
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
     const int grid = persistent_grid(tiles_o * tiles_t);
     if (grid <= 0) return SS_ERR_HIP;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    const int64_t Kb = K * elem_size(dtype);
     switch (dtype) {
     case SS_I8: return launch_dense<SS_I8>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, tiles_o, tiles_t, grid, hs);
     case SS_FP8_E4M3: return launch_dense<SS_FP8_E4M3>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, tiles_o, tiles_t, grid, hs);
@@ -660,28 +596,79 @@ extern "C" ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq
     return SS_ERR_DTYPE;
 }
 
-extern "C" ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w,
-                                       int64_t M, int64_t O, int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy, void* stream)
+ss_status launch_sparse_tile(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                             int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, hipStream_t hs)
 {
-    ss_status st = check_gemm(X_lifted, s_x, w_vals, s_w, M, O, K_lifted, dtype, Y, ldy);
-    if (st != SS_OK || M == 0 || O == 0) return st;
-    if (!w_meta) return SS_ERR_NULL;
-    if ((uintptr_t)w_meta & 15) return SS_ERR_SHAPE;
-    if (use_skinny(M, O))
-        return launch_sparse_skinny(X_lifted, s_x, w_vals, w_meta, s_w, M, O, K_lifted * elem_size(dtype), dtype, Y, ldy,
-                                    static_cast<hipStream_t>(stream));
     const int tiles_o = (int)((O + BO - 1) / BO), tiles_t = (int)((M + BT - 1) / BT);
     const int grid = persistent_grid(tiles_o * tiles_t);
     if (grid <= 0) return SS_ERR_HIP;
-    hipStream_t hs = static_cast<hipStream_t>(stream);
-    const int64_t Kpb = K_lifted * elem_size(dtype);
     switch (dtype) {
-    case SS_I8: return launch_sparse<SS_I8>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
-    case SS_FP8_E4M3: return launch_sparse<SS_FP8_E4M3>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
-    case SS_BF16: return launch_sparse<SS_BF16>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
-    case SS_FP16: return launch_sparse<SS_FP16>(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_I8: return launch_sparse<SS_I8>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_FP8_E4M3: return launch_sparse<SS_FP8_E4M3>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_BF16: return launch_sparse<SS_BF16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
+    case SS_FP16: return launch_sparse<SS_FP16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, tiles_o, tiles_t, grid, hs);
     }
     return SS_ERR_DTYPE;
+}
+
+}  // namespace ss
+
+static ss_status check_workspace(const void* workspace, size_t workspace_bytes)
+{
+    if (workspace_bytes > 0 && !workspace) return SS_ERR_NULL;
+    if ((uintptr_t)workspace & 15) return SS_ERR_WORKSPACE;
+    return SS_OK;
+}
+
+extern "C" size_t slide_gemm_workspace_bytes(int64_t M, int64_t O, int64_t K, ss_dtype dtype)
+{
+    if (!valid_dtype(dtype) || M <= 0 || O <= 0 || K <= 0 || (K * elem_size(dtype)) % KSTEP != 0) return 0;
+    const int64_t units = K * elem_size(dtype) / KSTEP;
+    const ss_plan p = plan_gemm(M, O, units, (size_t)-1);
+    return p.path == SS_PATH_MID ? mid_workspace_bytes(M, O, p.S) : 0;
+}
+
+extern "C" ss_status dense_gemm_ws(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t K,
+                                   ss_dtype dtype, void* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream)
+{
+    ss_status st = check_gemm(Xq, s_x, Wq, s_w, M, O, K, dtype, Y, ldy);
+    if (st == SS_OK) st = check_workspace(workspace, workspace_bytes);
+    if (st != SS_OK || M == 0 || O == 0) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int64_t Kb = K * elem_size(dtype);
+    const ss_plan p = plan_gemm(M, O, Kb / KSTEP, workspace_bytes);
+    if (p.path == SS_PATH_SKINNY) return launch_dense_skinny(Xq, s_x, Wq, s_w, M, O, Kb, dtype, Y, ldy, hs);
+    if (p.path == SS_PATH_MID) return launch_dense_mid(Xq, s_x, Wq, s_w, M, O, Kb, dtype, Y, ldy, workspace, p.S, hs);
+    return launch_dense_tile(Xq, s_x, Wq, s_w, M, O, Kb, dtype, Y, ldy, hs);
+}
+
+extern "C" ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t K,
+                                ss_dtype dtype, void* Y, int64_t ldy, void* stream)
+{
+    return dense_gemm_ws(Xq, s_x, Wq, s_w, M, O, K, dtype, Y, ldy, nullptr, 0, stream);
+}
+
+extern "C" ss_status slide_sparse_gemm_ws(const void* X_lifted, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w,
+                                          int64_t M, int64_t O, int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy, void* workspace,
+                                          size_t workspace_bytes, void* stream)
+{
+    ss_status st = check_gemm(X_lifted, s_x, w_vals, s_w, M, O, K_lifted, dtype, Y, ldy);
+    if (st == SS_OK) st = check_workspace(workspace, workspace_bytes);
+    if (st != SS_OK || M == 0 || O == 0) return st;
+    if (!w_meta) return SS_ERR_NULL;
+    if ((uintptr_t)w_meta & 15) return SS_ERR_SHAPE;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int64_t Kpb = K_lifted * elem_size(dtype);
+    const ss_plan p = plan_gemm(M, O, Kpb / KSTEP, workspace_bytes);
+    if (p.path == SS_PATH_SKINNY) return launch_sparse_skinny(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, hs);
+    if (p.path == SS_PATH_MID) return launch_sparse_mid(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, workspace, p.S, hs);
+    return launch_sparse_tile(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, hs);
+}
+
+extern "C" ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w,
+                                       int64_t M, int64_t O, int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy, void* stream)
+{
+    return slide_sparse_gemm_ws(X_lifted, s_x, w_vals, w_meta, s_w, M, O, K_lifted, dtype, Y, ldy, nullptr, 0, stream);
 }
 
 extern "C" const char* ss_status_string(ss_status s)
@@ -692,7 +679,7 @@ extern "C" const char* ss_status_string(ss_status s)
     case SS_ERR_BAD_PATTERN_N: return "pattern parameter N outside 2..8";
     case SS_ERR_SHAPE: return "bad shape, stride or alignment";
     case SS_ERR_DTYPE: return "unsupported dtype";
-    case SS_ERR_WORKSPACE: return "workspace";
+    case SS_ERR_WORKSPACE: return "workspace not 16-byte aligned";
     case SS_ERR_HIP: return "HIP runtime error";
     }
     return "unknown status";

@@ -67,14 +67,49 @@ __device__ inline uint32_t pack_bf16x2(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
-// Kernels for few tokens (gemm_skinny.hip).  The C entry points choose them for M <= 64, and for M <= 128 when
-// the 256 x 256 tile kernels would have fewer than 64 tiles to spread over the compute units (measured on the
-// Qwen2.5-7B shapes at M = 128: 26 vs 32 us for 3584 -> 4608, but 84 vs 38 us for 3584 -> 37888).
+// Kernels for few tokens (gemm_skinny.hip): one workgroup per 32..128 output channels streams their weights once.
 constexpr int64_t SS_SKINNY_MAX_M = 128;
-inline bool use_skinny(int64_t M, int64_t O) { return M <= 64 || (M <= SS_SKINNY_MAX_M && (O + 255) / 256 < 64); }
 ss_status launch_sparse_skinny(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
                                int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, hipStream_t stream);
 ss_status launch_dense_skinny(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, ss_dtype dtype,
                               void* Y, int64_t ldy, hipStream_t stream);
+
+
+// The 256 x 256 tile kernels (gemm.hip).
+ss_status launch_sparse_tile(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                             int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, hipStream_t stream);
+ss_status launch_dense_tile(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, ss_dtype dtype,
+                            void* Y, int64_t ldy, hipStream_t stream);
+
+// Kernels with 128 x 128 tiles (gemm_mid.hip) for shapes that give the 256 x 256 tile kernels too few tiles to
+// occupy the compute units.
+// S > 1 splits the k range over S workgroups per tile; their partial sums go through `ws`
+// (mid_workspace_bytes(M, O, S) bytes) and a second kernel adds them in a fixed order.
+ss_status launch_sparse_mid(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                            int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
+ss_status launch_dense_mid(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, ss_dtype dtype,
+                           void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
+int mid_splits(int64_t M, int64_t O, int64_t units, size_t ws_bytes);
+size_t mid_workspace_bytes(int64_t M, int64_t O, int S);
+inline int64_t mid_tiles(int64_t M, int64_t O) { return ((O + 127) / 128) * ((M + 127) / 128); }
+
+// Which kernel family a GEMM of M tokens x O channels over `units` 128-byte k units runs on, and in how many k
+// ranges (S > 1 only for SS_PATH_MID and only with a workspace).  Measured on the Qwen2.5-7B shapes (INT8, 6:8):
+//   M <= 32                      few-token kernels (7 to 9 us on 3584 -> 4608, where the others need 15 and 31);
+//   32 < M <= 64                 the same, unless the rows are long and can be split (18944 -> 3584 at M = 48:
+//                                53 us few-token, 23 us in 8 ranges of 128 x 128 tiles);
+//   up to 320 tiles of 128 x 128 those tiles (M = 256 on 3584 -> 4608: 17 us in 3 ranges, 33 us with 256 x 256
+//                                tiles; M = 1024 on 18944 -> 3584: 111 vs 150 us);
+//   beyond                       the 256 x 256 tile kernels (M = 2048 on 3584 -> 4608: 40 vs 57 us).
+enum ss_path { SS_PATH_SKINNY, SS_PATH_MID, SS_PATH_TILE };
+struct ss_plan { ss_path path; int S; };
+inline ss_plan plan_gemm(int64_t M, int64_t O, int64_t units, size_t ws_bytes)
+{
+    if (M <= 32) return {SS_PATH_SKINNY, 1};
+    if (M > 64 && mid_tiles(M, O) > 320) return {SS_PATH_TILE, 1};
+    const int S = mid_splits(M, O, units, ws_bytes);
+    if (M <= 64 && !(S > 1 && units >= 96)) return {SS_PATH_SKINNY, 1};
+    return {SS_PATH_MID, S};
+}
 
 }  // namespace ss

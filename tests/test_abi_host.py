@@ -53,6 +53,17 @@ def test_lifted_ld(lib):
     assert binding.load().slide_lifted_ld(64, 4, 7) == -1
 
 
+def test_gemm_workspace_bytes(lib):
+    # 64 KiB (128 x 128 partial sums of 4 bytes) per tile and k range; 0 where the k range is not split
+    w = binding.slide_gemm_workspace_bytes
+    assert w(16, 4608, 5376, "i8") == 0                       # few tokens: weights streamed once
+    assert w(8192, 4608, 5376, "i8") == 0                     # enough 256 x 256 tiles
+    assert w(128, 4608, 5376, "i8") % (36 * 65536) == 0 and w(128, 4608, 5376, "i8") > 0
+    assert w(256, 3584, 28416, "i8") % (56 * 65536) == 0 and w(256, 3584, 28416, "i8") > 0
+    assert w(48, 3584, 28416, "fp8") > 0 and w(48, 4608, 5376, "fp8") == 0    # 32 < M <= 64: only long rows
+    assert w(128, 4608, 100, "i8") == 0 and w(0, 4608, 5376, "i8") == 0 and w(128, 4608, 5376, "i8") == w(128, 4608, 2688, "bf16")
+
+
 def test_packed_sizes(lib):
     v, m = binding.slide_packed_sizes(512, 512, 4, "i8")
     assert (v, m) == (512 * 384, 512 * 96)
@@ -97,6 +108,11 @@ def test_argument_errors_return_codes(lib):
     # bf16 rows are counted in bytes: K = 64 is a whole 128-byte line, K = 32 is not; scales may be NULL only for bf16
     assert lib.dense_gemm(one, None, one, None, 16, 128, 32, 2, one, 128, None) == 3
     assert lib.dense_gemm(one, None, one, None, 16, 128, 128, 0, one, 128, None) == 1
+    # workspace variants: unaligned workspace, NULL workspace with a size
+    assert lib.dense_gemm_ws(one, one, one, one, 16, 128, 128, 0, one, 128, ctypes.c_void_p(24), 1024, None) == 5
+    assert lib.dense_gemm_ws(one, one, one, one, 16, 128, 128, 0, one, 128, None, 1024, None) == 1
+    assert lib.slide_sparse_gemm_ws(one, one, one, one, one, 16, 128, 128, 0, one, 128, ctypes.c_void_p(8), 64, None) == 5
+    assert lib.slide_sparse_gemm_ws(one, one, one, one, one, 16, 128, 100, 0, one, 128, one, 64, None) == 3
     # empty problems are fine and touch nothing
     assert lib.act_lift_quant(None, 0, 0, 64, 64, 4, 0, None, None, None) == 0
     assert lib.dense_gemm(None, None, None, None, 0, 128, 128, 0, None, 128, None) == 0

@@ -15,7 +15,7 @@ pytestmark = pytest.mark.gpu
 N_SAMPLE = 96
 
 
-def _run_and_sample(M, K, O, N, dtype, seed):
+def _run_and_sample(M, K, O, N, dtype, seed, use_workspace=False):
     X = synth.activations(M, K, seed)
     W = synth.weights(O, K, seed)
     Xd, Wd = dev(X), dev(W)
@@ -23,10 +23,16 @@ def _run_and_sample(M, K, O, N, dtype, seed):
     del Wd
     w_vals, w_meta, viol = binding.slide_decompose(Wq, N, dtype, count_violations=True)
     XL, s_x = binding.act_lift_quant(Xd, N, dtype)
-    Y = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype)
-    Y2 = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype)
+    ws_s = ws_d = None
+    if use_workspace:                                            # k range split over workgroups where the library would
+        ns, nd = binding.slide_gemm_workspace_bytes(M, O, XL.shape[1], dtype), binding.slide_gemm_workspace_bytes(M, O, K, dtype)
+        assert ns > 0 and nd > 0
+        ws_s = torch.empty((ns,), dtype=torch.uint8, device=XL.device)
+        ws_d = torch.empty((nd,), dtype=torch.uint8, device=XL.device)
+    Y = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype, workspace=ws_s)
+    Y2 = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype, workspace=ws_s)
     Xq, s_x2 = binding.act_lift_quant(Xd, 2, dtype)
-    Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype)
+    Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype, workspace=ws_d)
     assert int(host(viol)[0]) == 0
     assert torch.equal(Y, Y2)                                    # deterministic from launch to launch
     rng = np.random.default_rng(seed + 12345)
@@ -85,3 +91,17 @@ def test_qwen25_7b_float_m8192(dtype, name, K, O):
     Y, Yd, sample, ref = _run_and_sample(8192, K, O, 4, dtype, seed=7)
     _float_gemm_check(sample(Y), ref, dtype)
     _float_gemm_check(sample(Yd), ref, dtype)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16"])
+@pytest.mark.parametrize("M", [128, 256])
+@pytest.mark.parametrize("name,K,O", [synth.QWEN25_7B[0], synth.QWEN25_7B[3]])
+def test_qwen25_7b_mid_m_with_workspace(dtype, M, name, K, O):
+    """Token counts between decode and prefill: 128 x 128 tiles with the k range split through a workspace."""
+    Y, Yd, sample, ref = _run_and_sample(M, K, O, 4, dtype, seed=M + 1, use_workspace=True)
+    if dtype == "i8":
+        assert np.array_equal(sample(Y), ref["Y"])
+        assert torch.equal(Y, Yd)
+    else:
+        _float_gemm_check(sample(Y), ref, dtype)
+        _float_gemm_check(sample(Yd), ref, dtype)

@@ -282,10 +282,11 @@ def test_sparse_and_dense_gemm_float(dtype, N, M, O, K):
 
 
 # ------------------------------------------------------------------ kernel selection boundaries
-@pytest.mark.parametrize("M,O", [(32, 128), (33, 160), (64, 8192), (65, 8192), (65, 16384 + 256), (128, 512), (129, 512), (128, 16384)])
+@pytest.mark.parametrize("M,O", [(32, 128), (33, 160), (64, 8192), (65, 8192), (65, 128 * 320), (65, 128 * 321), (128, 512), (129, 512),
+                                 (128, 128 * 320), (129, 128 * 161), (256, 128 * 160), (257, 128 * 107)])
 def test_gemm_kernel_selection_boundaries_int8(M, O):
-    """Token counts around the switch between the few-token kernels (M <= 64, or M <= 128 with few channel
-    tiles) and the 256 x 256 tile kernels: the result must not depend on which one runs."""
+    """Shapes around the switches between the few-token kernels (M <= 64), the 128 x 128-tile kernels (up to 320
+    such tiles) and the 256 x 256 tile kernels: the result must not depend on which one runs."""
     N, K = 4, 256
     rng = np.random.default_rng(M * 7 + O)
     Wq = rng.integers(-127, 128, size=(O, K)).astype(np.int8)
@@ -300,6 +301,56 @@ def test_gemm_kernel_selection_boundaries_int8(M, O):
     assert np.array_equal(bits16(Ys), exp)
     Yd = binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8")
     assert np.array_equal(bits16(Yd), exp)
+
+
+# ------------------------------------------------------------------ split k range with a caller-owned workspace
+def _workspace(M, O, Kp, dtype, fill, scale=1.0):
+    need = binding.slide_gemm_workspace_bytes(M, O, Kp, dtype)
+    n = max(16, int(need * scale) // 16 * 16)
+    return need, torch.full((n,), fill, dtype=torch.uint8, device=DEV)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
+@pytest.mark.parametrize("N,M,O,K", [(4, 100, 384, 2048),       # 3 tiles of 128 x 128, K' = 3072: 24 units
+                                     (4, 48, 200, 8192),        # 32 < M <= 64 with long rows
+                                     (3, 300, 130, 3072),       # ragged tokens and channels, K' = 4096
+                                     (2, 129, 257, 4096),       # native 2:4
+                                     (5, 64, 128, 10240)])      # K' = 16384
+def test_gemm_split_k_with_workspace(dtype, N, M, O, K):
+    """The 128 x 128-tile kernels with the k range of a tile split over several workgroups: partial sums go
+    through the caller's workspace and are added in a fixed order.  INT8 must equal the oracle bit for bit (and
+    so the call without workspace); floats stay within the GEMM tolerance and are reproducible bit for bit."""
+    X = synth.activations(M, K, seed=M + K, n_outliers=2)
+    W = synth.weights(O, K, seed=O + N)
+    ref = so.linear_reference(X, W, N, dtype)
+    Xd, Wd = dev(X), dev(W)
+    Wq, s_w = binding.slide_prune_quant(Wd, N, dtype)
+    w_vals, w_meta = binding.slide_decompose(Wq, N, dtype)
+    XL, s_x = binding.act_lift_quant(Xd, N, dtype)
+    Xq, s_x2 = binding.act_lift_quant(Xd, 2, dtype)
+    need, ws = _workspace(M, O, XL.shape[1], dtype, fill=0xFF)             # 0xFF..: NaN patterns, contents must not matter
+    assert need > 0, "shape chosen so that the k range is split"
+    Ys = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype, workspace=ws)
+    need_d, ws_d = _workspace(M, O, K, dtype, fill=0x7F)
+    Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype, workspace=ws_d)
+    if dtype == "i8":
+        assert np.array_equal(bits16(Ys), ref["Y"]) and np.array_equal(bits16(Yd), ref["Y"])
+        assert torch.equal(Ys, binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype))
+    else:
+        _float_gemm_check(bits16(Ys), ref, dtype)
+        _float_gemm_check(bits16(Yd), ref, dtype)
+    # same bits on a second run over the used workspace, and with a workspace that only holds fewer ranges
+    assert torch.equal(Ys, binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype, workspace=ws))
+    assert torch.equal(Yd, binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype, workspace=ws_d))
+    _, small = _workspace(M, O, XL.shape[1], dtype, fill=0x11, scale=0.6)
+    Y2 = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype, workspace=small)
+    if dtype == "i8":
+        assert torch.equal(Y2, Ys)
+    else:
+        _float_gemm_check(bits16(Y2), ref, dtype)
+    tiny = torch.zeros((16,), dtype=torch.uint8, device=DEV)                # too small for any split: plain path
+    Y3 = binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype, workspace=tiny)
+    assert torch.equal(Y3, binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype))
 
 
 # ------------------------------------------------------------------ seeded random shapes
