@@ -30,6 +30,7 @@
 #include "packed_layout.h"
 #include "mma_types.h"
 #include "lds_pipe.h"
+#include "device_info.h"
 #include <type_traits>
 
 
@@ -538,9 +539,7 @@ using namespace ss;
 // one persistent workgroup per compute unit of the current device (fewer if there are fewer tiles)
 static int persistent_grid(int ntiles)
 {
-    int dev = 0, cus = 0;
-    if (hipGetDevice(&dev) != hipSuccess) return -1;
-    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus <= 0) return -1;
+    const int cus = cu_count();
     return ntiles < cus ? ntiles : cus;
 }
 
@@ -561,7 +560,7 @@ template <int DT>
 static ss_status launch_dense(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, void* Y,
                               int64_t ldy, int tiles_o, int tiles_t, int grid, hipStream_t stream)
 {
-    if (hipFuncSetAttribute((const void*)k_dense<DT>, hipFuncAttributeMaxDynamicSharedMemorySize, D_LDS) != hipSuccess) return SS_ERR_HIP;
+    if (allow_dynamic_lds<k_dense<DT>>(D_LDS) != SS_OK) return SS_ERR_HIP;
     hipLaunchKernelGGL((k_dense<DT>), dim3(grid), dim3(G_THREADS), D_LDS, stream, static_cast<const uint8_t*>(Xq), s_x,
                        static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, tiles_o, tiles_t);
     return launch_status();
@@ -571,7 +570,7 @@ template <int DT>
 static ss_status launch_sparse(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
                                int64_t Kpb, void* Y, int64_t ldy, int tiles_o, int tiles_t, int grid, hipStream_t stream)
 {
-    if (hipFuncSetAttribute((const void*)k_sparse<DT>, hipFuncAttributeMaxDynamicSharedMemorySize, S_LDS) != hipSuccess) return SS_ERR_HIP;
+    if (allow_dynamic_lds<k_sparse<DT>>(S_LDS) != SS_OK) return SS_ERR_HIP;
     hipLaunchKernelGGL((k_sparse<DT>), dim3(grid), dim3(G_THREADS), S_LDS, stream, static_cast<const uint8_t*>(XL), s_x,
                        static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy,
                        tiles_o, tiles_t);

@@ -17,6 +17,7 @@
 #include "packed_layout.h"
 #include "mma_types.h"
 #include "lds_pipe.h"
+#include "device_info.h"
 
 namespace ss {
 
@@ -310,13 +311,6 @@ __global__ __launch_bounds__(MD_THREADS) void k_dense_mid(const uint8_t* __restr
 
 using namespace ss;
 
-static int mid_cu_count()
-{
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    return cus;
-}
-
 template <int DT>
 static ss_status launch_mid_reduce(const void* ws, int S, int64_t ntiles, const float* s_x, const float* s_w, int64_t M, int64_t O, void* Y,
                                    int64_t ldy, int tiles_t, hipStream_t stream)
@@ -333,7 +327,7 @@ static ss_status launch_sparse_mid_dt(const void* XL, const float* s_x, const vo
     const int tiles_t = (int)((M + MD_TILE - 1) / MD_TILE);
     const int64_t ntiles = (O + PANEL - 1) / PANEL * tiles_t;
     constexpr int lds = MD_S_RING * MD_S_UNIT;
-    if (hipFuncSetAttribute((const void*)k_sparse_mid<DT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return SS_ERR_HIP;
+    if (allow_dynamic_lds<k_sparse_mid<DT>>(lds) != SS_OK) return SS_ERR_HIP;
     hipLaunchKernelGGL((k_sparse_mid<DT>), dim3((unsigned)ntiles, (unsigned)S), dim3(MD_THREADS), lds, stream, static_cast<const uint8_t*>(XL), s_x,
                        static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy,
                        tiles_t, ws);
@@ -348,7 +342,7 @@ static ss_status launch_dense_mid_dt(const void* Xq, const float* s_x, const voi
     const int tiles_t = (int)((M + MD_TILE - 1) / MD_TILE);
     const int64_t ntiles = (O + PANEL - 1) / PANEL * tiles_t;
     constexpr int lds = MD_D_RING * MD_D_UNIT;
-    if (hipFuncSetAttribute((const void*)k_dense_mid<DT>, hipFuncAttributeMaxDynamicSharedMemorySize, lds) != hipSuccess) return SS_ERR_HIP;
+    if (allow_dynamic_lds<k_dense_mid<DT>>(lds) != SS_OK) return SS_ERR_HIP;
     hipLaunchKernelGGL((k_dense_mid<DT>), dim3((unsigned)ntiles, (unsigned)S), dim3(MD_THREADS), lds, stream, static_cast<const uint8_t*>(Xq), s_x,
                        static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, tiles_t, ws);
     if (launch_status() != SS_OK) return SS_ERR_HIP;
@@ -364,7 +358,7 @@ namespace ss {
 int mid_splits(int64_t M, int64_t O, int64_t units, size_t ws_bytes)
 {
     const int64_t ntiles = mid_tiles(M, O);
-    int64_t S = mid_cu_count() / ntiles;
+    int64_t S = cu_count() / ntiles;
     if (S > units / 8) S = units / 8;
     const int64_t fit = (int64_t)(ws_bytes / ((size_t)ntiles * MD_WS_TILE));
     if (S > fit) S = fit;

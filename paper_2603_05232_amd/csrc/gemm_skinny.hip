@@ -18,6 +18,7 @@
 #include "ss_common.h"
 #include "packed_layout.h"
 #include "mma_types.h"
+#include "device_info.h"
 
 namespace ss {
 
@@ -287,20 +288,12 @@ using namespace ss;
 
 // Fragments per workgroup: as many as leave every compute unit at least one workgroup; wide token blocks keep it
 // small because of their accumulators.
-static int cu_count();
 static int pick_fpw(int64_t frags, int tb_max_fpw)
 {
     const int cus = cu_count();
     int fpw = 4;
     while (fpw > 1 && (fpw > tb_max_fpw || frags / fpw < cus)) fpw >>= 1;
     return fpw;
-}
-
-static int cu_count()
-{
-    int dev = 0, cus = 256;
-    if (hipGetDevice(&dev) == hipSuccess) (void)hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev);
-    return cus;
 }
 
 template <int DT, int TB, int FPW>
