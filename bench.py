@@ -40,6 +40,9 @@ def parse():
     ap.add_argument("--warmup", type=int, default=25)
     ap.add_argument("--tokens", type=int, default=M_TOKENS)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--act-dtype", choices=["fp32", "bf16"], default="fp32",
+                    help="storage type of the activations handed to act_lift_quant (the configuration says fp32; bf16 is what a "
+                         "bf16 model would hand over and halves the bytes the lifting kernel reads)")
     ap.add_argument("--copy-calibration", action="store_true",
                     help="also run a plain elementwise copy of known size (256 MiB read + 256 MiB written per launch), the "
                          "yardstick that scales the FETCH_SIZE / WRITE_SIZE counters of a rocprofv3 --pmc run of this script")
@@ -166,6 +169,8 @@ def main():
     state = []
     for li, (name, K, O) in enumerate(layers):
         X = torch.from_numpy(synth.activations(M, K, seed=li)).to(dev)
+        if args.act_dtype == "bf16":
+            X = X.to(torch.bfloat16)
         W = torch.from_numpy(synth.weights(O, K, seed=li)).to(dev)
         Wq, s_w = binding.slide_prune_quant(W, N, "i8")
         w_vals, w_meta, viol = binding.slide_decompose(Wq, N, "i8", count_violations=True)
@@ -260,7 +265,8 @@ def main():
     lift_ms = float(k_sparse[:, 0].sum())
     quant_ms = float(k_dense[:, 0].sum())
     executed_tops = (hw_ops / 2) / (gemm_ms * 1e-3) * 1e-12          # MACs actually issued x 2
-    lift_bytes = sum(M * (s["K"] * 4 + s["Kp"] + 4) for s in state)
+    in_bytes = 4 if args.act_dtype == "fp32" else 2
+    lift_bytes = sum(M * (s["K"] * in_bytes + s["Kp"] + 4) for s in state)
     per_layer = {s["name"]: {"K": s["K"], "O": s["O"], "K_lifted": s["Kp"],
                              "lift_ms": float(k_sparse[i, 0]), "sparse_gemm_ms": float(k_sparse[i, 1]),
                              "quant_ms": float(k_dense[i, 0]), "dense_gemm_ms": float(k_dense[i, 1]),
@@ -274,7 +280,7 @@ def main():
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_sparse * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
         "config": {"workload": f"Qwen2.5-7B linears (qkv,o,gate_up,down), 6:8 INT8, M={M} tokens: act_lift_quant + slide_sparse_gemm per layer",
-                   "pattern": "6:8", "tokens": M},
+                   "pattern": "6:8", "tokens": M, "activations": args.act_dtype},
         "value_definition": "sum over layers of 2*M*O*K_lifted (hardware-counted ops) / time of the whole step (lifting included)",
         "gemm_only_hw_tops": hw_ops / (gemm_ms * 1e-3) * 1e-12,
         "gemm_only_useful_tops": useful_ops / (gemm_ms * 1e-3) * 1e-12,
@@ -296,7 +302,7 @@ def main():
                            "unit": "TFLOP/s", "frac": useful_ops / (dgemm_ms * 1e-3) * 1e-12 / PEAK_INT8_DENSE_TOPS,
                            "kernel": "ss::k_dense<0> (dense_gemm, INT8)"},
         "roofline_lift": {"bound": "hbm", "achieved": lift_bytes / (lift_ms * 1e-3) * 1e-9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                          "frac": lift_bytes / (lift_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, "kernel": "k_act_lift_quant (fp32 in, int8 out)"},
+                          "frac": lift_bytes / (lift_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, "kernel": f"k_act_lift_quant ({args.act_dtype} in, int8 out)"},
     }
     if args.vendor_baseline:
         vend = {}

@@ -29,7 +29,7 @@ template <> struct InVec<uint16_t> {          // bf16 bits
 __device__ inline float load_scalar(const float* p) { return *p; }
 __device__ inline float load_scalar(const uint16_t* p) { return bf16_bits_to_f32(*p); }
 
-__device__ inline float block_absmax(float v, float* red)
+template <int THREADS> __device__ inline float block_absmax(float v, float* red)
 {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
@@ -38,7 +38,7 @@ __device__ inline float block_absmax(float v, float* red)
     __syncthreads();
     float m = red[0];
 #pragma unroll
-    for (int w = 1; w < LQ_THREADS / 64; ++w) m = fmaxf(m, red[w]);
+    for (int w = 1; w < THREADS / 64; ++w) m = fmaxf(m, red[w]);
     return m;
 }
 
@@ -60,17 +60,19 @@ template <int OUT> __device__ inline uint32_t quant1(float x, float r)
     }
 }
 
-// MAXV > 0: vector loads, row kept in registers (needs K <= MAXV * LQ_THREADS * VecN, 16-byte
-// aligned rows).  MAXV == 0: scalar loads, second pass re-reads the row.
-template <typename TIN, int OUT, int MAXV>
-__global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __restrict__ X, int64_t ldx, int K, int N,
+// MAXV > 0: vector loads, row kept in registers (needs K <= MAXV * THREADS * VecN, 16-byte
+// aligned rows).  MAXV == 0: scalar loads, second pass re-reads the row.  Long rows take more
+// threads per token rather than more registers per thread: the loads of a token are all in
+// flight at once either way, but fewer registers leave room for more tokens per compute unit.
+template <typename TIN, int OUT, int MAXV, int THREADS>
+__global__ __launch_bounds__(THREADS) void k_act_lift_quant(const TIN* __restrict__ X, int64_t ldx, int K, int N,
                                                                 uint8_t* __restrict__ XL, float* __restrict__ s_x, int Kp, int Kz)
 {
     // Kp: stored width of a lifted row (whole 128-byte units); Kz >= n_g * 2N + 8 / ES: elements
     // of the quantised row held in LDS, those at and beyond K being zero (zero-completed last block)
     constexpr int ES = OUT >= 2 ? 2 : 1;                 // output element bytes
     extern __shared__ uint32_t lds[];                     // Kz * ES bytes
-    __shared__ float red[LQ_THREADS / 64];
+    __shared__ float red[THREADS / 64];
     const int64_t m = blockIdx.x;
     const TIN* x = X + m * ldx;
     const int t = threadIdx.x;
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __rest
         const typename IV::V* xv = reinterpret_cast<const typename IV::V*>(x);
 #pragma unroll
         for (int i = 0; i < MAXV; ++i) {
-            const int idx = t + i * LQ_THREADS;
+            const int idx = t + i * THREADS;
             if (idx < nvec) {
                 v[i] = xv[idx];
                 if constexpr (OUT < 2) {
@@ -95,11 +97,11 @@ __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __rest
             }
         }
     } else if constexpr (OUT < 2) {
-        for (int k = t; k < K; k += LQ_THREADS) amax = fmaxf(amax, fabsf(load_scalar(x + k)));
+        for (int k = t; k < K; k += THREADS) amax = fmaxf(amax, fabsf(load_scalar(x + k)));
     }
     float r = 0.0f;
     if constexpr (OUT < 2) {
-        amax = block_absmax(amax, red);
+        amax = block_absmax<THREADS>(amax, red);
         constexpr float QMAX = OUT == 0 ? 127.0f : 448.0f;
         float s = 1.0f;
         if (amax > 0.0f) { r = QMAX / amax; s = amax / QMAX; }
@@ -110,7 +112,7 @@ __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __rest
     if constexpr (MAXV > 0) {
 #pragma unroll
         for (int i = 0; i < MAXV; ++i) {
-            const int idx = t + i * LQ_THREADS;
+            const int idx = t + i * THREADS;
             if (idx < nvec) {
                 float f[IV::N]; IV::unpack(v[i], f);
                 if constexpr (ES == 1) {
@@ -130,18 +132,18 @@ __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __rest
     } else {
         if constexpr (ES == 1) {
             uint8_t* l8 = reinterpret_cast<uint8_t*>(lds);
-            for (int k = t; k < K; k += LQ_THREADS) l8[k] = (uint8_t)quant1<OUT>(load_scalar(x + k), r);
+            for (int k = t; k < K; k += THREADS) l8[k] = (uint8_t)quant1<OUT>(load_scalar(x + k), r);
         } else {
             uint16_t* l16 = reinterpret_cast<uint16_t*>(lds);
-            for (int k = t; k < K; k += LQ_THREADS) l16[k] = (uint16_t)quant1<OUT>(load_scalar(x + k), r);
+            for (int k = t; k < K; k += THREADS) l16[k] = (uint16_t)quant1<OUT>(load_scalar(x + k), r);
         }
     }
     if constexpr (ES == 1) {
         uint8_t* l8 = reinterpret_cast<uint8_t*>(lds);
-        for (int k = K + t; k < Kz; k += LQ_THREADS) l8[k] = 0;
+        for (int k = K + t; k < Kz; k += THREADS) l8[k] = 0;
     } else {
         uint16_t* l16 = reinterpret_cast<uint16_t*>(lds);
-        for (int k = K + t; k < Kz; k += LQ_THREADS) l16[k] = 0;
+        for (int k = K + t; k < Kz; k += THREADS) l16[k] = 0;
     }
     __syncthreads();
 
@@ -152,7 +154,7 @@ __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __rest
     const int ng = (K + 2 * N - 1) / (2 * N);
     uint4* out = reinterpret_cast<uint4*>(XL + m * (int64_t)Kp * ES);
     if constexpr (ES == 1) {
-        for (int c = t; c < nwin / 4; c += LQ_THREADS) {
+        for (int c = t; c < nwin / 4; c += THREADS) {
             int j = 4 * c, g = j / nw1, l = j - g * nw1;
             uint32_t w[4];
 #pragma unroll
@@ -169,7 +171,7 @@ __global__ __launch_bounds__(LQ_THREADS) void k_act_lift_quant(const TIN* __rest
         }
     } else {
         // 16-bit elements: a window is 8 bytes = elements b..b+3, b even -> two aligned dwords
-        for (int c = t; c < nwin / 2; c += LQ_THREADS) {
+        for (int c = t; c < nwin / 2; c += THREADS) {
             int j = 2 * c, g = j / nw1, l = j - g * nw1;
             uint32_t w[4];
 #pragma unroll
@@ -199,15 +201,17 @@ static ss_status launch_lift(const void* X, int64_t M, int64_t K, int64_t ldx, i
     const int Kz = (int)lift_lds_elems(K, N, ES);
     const size_t lds_bytes = (size_t)Kz * ES;
     const bool vec_ok = (K % IV::N == 0) && (ldx % IV::N == 0) && (((uintptr_t)X & 15) == 0);
-    const int64_t per_thread = (K / IV::N + LQ_THREADS - 1) / LQ_THREADS;
-    dim3 grid((unsigned)M), block(LQ_THREADS);
+    const int64_t nvec = K / IV::N;                           // 16-byte vectors per row
+    dim3 grid((unsigned)M);
     const TIN* x = static_cast<const TIN*>(X);
     uint8_t* xl = static_cast<uint8_t*>(XL);
-#define SS_LQ(MAXV) hipLaunchKernelGGL((k_act_lift_quant<TIN, OUT, MAXV>), grid, block, lds_bytes, st, x, ldx, (int)K, N, xl, s_x, Kp, Kz)
-    if (vec_ok && per_thread <= 4) SS_LQ(4);
-    else if (vec_ok && per_thread <= 10) SS_LQ(10);
-    else if (vec_ok && per_thread <= 20) SS_LQ(20);
-    else SS_LQ(0);
+#define SS_LQ(MAXV, T) hipLaunchKernelGGL((k_act_lift_quant<TIN, OUT, MAXV, T>), grid, dim3(T), lds_bytes, st, x, ldx, (int)K, N, xl, s_x, Kp, Kz)
+    if (vec_ok && nvec <= 4 * 256) SS_LQ(4, 256);
+    else if (vec_ok && nvec <= 4 * 512) SS_LQ(4, 512);
+    else if (vec_ok && nvec <= 5 * 1024) SS_LQ(5, 1024);
+    else if (vec_ok && nvec <= 10 * 1024) SS_LQ(10, 1024);
+    else if (vec_ok && nvec <= 20 * 1024) SS_LQ(20, 1024);
+    else SS_LQ(0, 256);
 #undef SS_LQ
     return launch_status();
 }
@@ -228,7 +232,7 @@ __global__ __launch_bounds__(LQ_THREADS) void k_prune_quant(const TIN* __restric
     if constexpr (OUT < 2) {
         float amax = 0.0f;
         for (int k = t; k < K; k += LQ_THREADS) amax = fmaxf(amax, fabsf(load_scalar(w + k)));
-        amax = block_absmax(amax, red);               // the row maximum always survives pruning
+        amax = block_absmax<LQ_THREADS>(amax, red);   // the row maximum always survives pruning
         constexpr float QMAX = OUT == 0 ? 127.0f : 448.0f;
         float s = 1.0f;
         if (amax > 0.0f) { r = QMAX / amax; s = amax / QMAX; }

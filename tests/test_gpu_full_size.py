@@ -105,3 +105,34 @@ def test_qwen25_7b_mid_m_with_workspace(dtype, M, name, K, O):
     else:
         _float_gemm_check(sample(Y), ref, dtype)
         _float_gemm_check(sample(Yd), ref, dtype)
+
+
+@pytest.mark.parametrize("M,O", [(3, 40), (65, 16)])
+def test_longest_rows_int8(M, O):
+    """Rows at the documented maximum of the GEMMs (2^23 bytes; here K' = 65535 units of 128 bytes) on the
+    few-token kernels (M = 3) and the 128 x 128-tile kernels with and without split (M = 65): 32-bit lane offsets
+    and unit counters at their limits.  Operands are generated quantised (the lifting kernel keeps a row in LDS and
+    stops at 64 KiB); the oracle lifts and multiplies."""
+    from oracle import gemm_ref
+    N = 4
+    K = 65535 * 128 * 2 // 3                                   # K' = 1.5 K = 65535 * 128
+    assert K % 8 == 0 and so.lifted_k(K, N) == 65535 * 128 == binding.slide_lifted_ld(K, N, "i8")
+    rng = np.random.default_rng(M)
+    Wq = rng.integers(-127, 128, size=(O, K), dtype=np.int8)
+    Wq.reshape(O, K // 8, 8)[:, :, rng.permutation(8)[:2]] = 0    # two zeros per block of 8 (same positions everywhere)
+    Wq.reshape(O, K // 8, 8)[:, ::3, 5] = 0                       # some blocks with three
+    Xq = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+    s_x = rng.uniform(0.001, 0.01, M).astype(np.float32)
+    s_w = rng.uniform(1e-5, 1e-4, O).astype(np.float32)
+    exp = so.epilogue(gemm_ref.gemm_i8_i64(Xq, Wq), s_x, s_w, "i8")
+    w_vals, w_meta, viol = binding.slide_decompose(dev(Wq), N, "i8", count_violations=True)
+    assert int(host(viol)[0]) == 0
+    XL = dev(so.lift(Xq, N))
+    Y = binding.slide_sparse_gemm(XL, dev(s_x), w_vals, w_meta, dev(s_w), O, "i8")
+    assert np.array_equal(bits16(Y), exp)
+    n = binding.slide_gemm_workspace_bytes(M, O, XL.shape[1], "i8")
+    if n:
+        ws = torch.empty((n,), dtype=torch.uint8, device=XL.device)
+        assert np.array_equal(bits16(binding.slide_sparse_gemm(XL, dev(s_x), w_vals, w_meta, dev(s_w), O, "i8", workspace=ws)), exp)
+    if K % 128 == 0:
+        assert np.array_equal(bits16(binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8")), exp)
