@@ -166,7 +166,7 @@ def main():
     N = N_PATTERN
 
     # ---- untimed set-up: synthetic tensors, offline weight path
-    state = []
+    state, offline = [], []
     for li, (name, K, O) in enumerate(layers):
         X = torch.from_numpy(synth.activations(M, K, seed=li)).to(dev)
         if args.act_dtype == "bf16":
@@ -174,6 +174,15 @@ def main():
         W = torch.from_numpy(synth.weights(O, K, seed=li)).to(dev)
         Wq, s_w = binding.slide_prune_quant(W, N, "i8")
         w_vals, w_meta, viol = binding.slide_decompose(Wq, N, "i8", count_violations=True)
+        # the offline weight path once more under HIP events (reported, not part of the step)
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        ev[0].record()
+        binding.slide_prune_quant(W, N, "i8")
+        ev[1].record()
+        binding.slide_decompose(Wq, N, "i8")
+        ev[2].record()
+        torch.cuda.synchronize()
+        offline.append((name, O * K, ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])))
         del W
         Kp = binding.slide_lifted_k(K, N)
         st = dict(name=name, K=K, O=O, Kp=Kp, X=X, Wq=Wq, s_w=s_w, w_vals=w_vals, w_meta=w_meta,
@@ -293,6 +302,12 @@ def main():
         "dense_ms_per_step": t_dense * 1e3, "lift_ms": lift_ms, "quant_only_ms": quant_ms,
         "sparse_equals_dense_bitwise": same,
         "per_layer": per_layer,
+        "offline_weight_path": {"note": "slide_prune_quant (fp32 weights in) and slide_decompose (Alg. 2 + 2:4 compression + packing), one "
+                                        "launch each per layer; GB/s = bytes of the quantised weight matrix O*K / time",
+                                "prune_quant_ms": {n: p for n, _, p, _ in offline},
+                                "decompose_ms": {n: d for n, _, _, d in offline},
+                                "decompose_GBps_of_weight_bytes": sum(b for _, b, _, _ in offline) / sum(d for _, _, _, d in offline) * 1e-6,
+                                "prune_quant_GBps_of_weight_bytes": sum(b for _, b, _, _ in offline) / sum(p for _, _, p, _ in offline) * 1e-6},
         "roofline": {"bound": "mfma", "achieved": executed_tops, "peak": PEAK_INT8_DENSE_TOPS, "unit": "TFLOP/s",
                      "frac": executed_tops / PEAK_INT8_DENSE_TOPS, "traffic": SPARSE_GEMM_TRAFFIC,
                      "kernel": "ss::k_sparse<0> (slide_sparse_gemm, INT8), mean over the four layer launches of a step",
