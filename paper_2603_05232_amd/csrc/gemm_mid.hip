@@ -136,11 +136,27 @@ __global__ __launch_bounds__(MD_THREADS) void k_mid_reduce(const v4i* __restrict
     acc_t a;
 #pragma unroll
     for (int r = 0; r < 16; ++r) a[r] = 0;
-    for (int s = 0; s < S; ++s) {
-        const v4i* src = ws + (((s * ntiles + tile) * MD_WAVES + wave) * 16 + ft * 4) * 64 + lane;
+    const v4i* src = ws + ((tile * MD_WAVES + wave) * 16 + ft * 4) * 64 + lane;
+    const int64_t range_stride = ntiles * MD_WAVES * 16 * 64;             // 16-byte groups between consecutive k ranges
+    // four ranges per trip: sixteen loads in flight per thread, added in range order
+    int s = 0;
+    for (; s + 4 <= S; s += 4) {
+        quad_t q[4][4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4) q[d][r4] = __builtin_bit_cast(quad_t, src[(s + d) * range_stride + r4 * 64]);
+#pragma unroll
+        for (int d = 0; d < 4; ++d)
+#pragma unroll
+            for (int r4 = 0; r4 < 4; ++r4)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) a[4 * r4 + e] += q[d][r4][e];
+    }
+    for (; s < S; ++s) {
 #pragma unroll
         for (int r4 = 0; r4 < 4; ++r4) {
-            const quad_t q = __builtin_bit_cast(quad_t, src[r4 * 64]);
+            const quad_t q = __builtin_bit_cast(quad_t, src[s * range_stride + r4 * 64]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) a[4 * r4 + e] += q[e];
         }

@@ -1,4 +1,4 @@
-// slide_sparse_gemm and dense_gemm for few tokens (M <= 128): the decode regime, bound by streaming the
+// slide_sparse_gemm and dense_gemm for few tokens (M <= 64): the decode regime, bound by streaming the
 // weights from HBM once, not by the matrix cores.
 //
 // A workgroup of four wavefronts owns FPW x 32 output channels (FPW matrix-instruction fragments, FPW = 1, 2
@@ -286,13 +286,12 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* _
 
 using namespace ss;
 
-// Fragments per workgroup: as many as leave every compute unit at least one workgroup; wide token blocks keep it
-// small because of their accumulators.
-static int pick_fpw(int64_t frags, int tb_max_fpw)
+// Fragments per workgroup: as many (4, 2 or 1) as leave every compute unit at least one workgroup.
+static int pick_fpw(int64_t frags)
 {
     const int cus = cu_count();
     int fpw = 4;
-    while (fpw > 1 && (fpw > tb_max_fpw || frags / fpw < cus)) fpw >>= 1;
+    while (fpw > 1 && frags / fpw < cus) fpw >>= 1;
     return fpw;
 }
 
@@ -325,19 +324,18 @@ static ss_status launch_dense_one(const void* Xq, const float* s_x, const void* 
     return launch_status();
 }
 
-// token blocks of 32: 1 (M <= 32), 2 (M <= 64) or 4; with 4 token blocks at most 2 fragments (128 accumulator registers)
+// token blocks of 32: 1 (M <= 32) or 2 (M <= 64)
 template <int DT>
 static ss_status launch_sparse_dt(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
                                   int64_t Kpb, void* Y, int64_t ldy, hipStream_t st)
 {
     const int64_t frags = (O + PANEL - 1) / PANEL * FRAGS_PER_PANEL;
-    const int tb = M <= 32 ? 1 : M <= 64 ? 2 : 4;
-    const int fpw = pick_fpw(frags, tb == 4 ? 2 : 4);
+    const int fpw = pick_fpw(frags);
 #define SS_GO(TB, FPW) return launch_sparse_one<DT, TB, FPW>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, st)
-    if (tb == 1) { if (fpw == 4) SS_GO(1, 4); if (fpw == 2) SS_GO(1, 2); SS_GO(1, 1); }
-    if (tb == 2) { if (fpw == 4) SS_GO(2, 4); if (fpw == 2) SS_GO(2, 2); SS_GO(2, 1); }
-    if (fpw == 2) SS_GO(4, 2);
-    SS_GO(4, 1);
+    if (M <= 32) { if (fpw == 4) SS_GO(1, 4); if (fpw == 2) SS_GO(1, 2); SS_GO(1, 1); }
+    if (fpw == 4) SS_GO(2, 4);
+    if (fpw == 2) SS_GO(2, 2);
+    SS_GO(2, 1);
 #undef SS_GO
 }
 
@@ -348,8 +346,7 @@ static ss_status launch_dense_dt(const void* Xq, const float* s_x, const void* W
     // One fragment per workgroup: the dense kernel stages its weight lines through LDS, and more fragments per
     // workgroup cost more in occupancy than they save in token re-reads (measured: 21 vs 35 us on 3584 -> 37888).
     if (M <= 32) return launch_dense_one<DT, 1, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, st);
-    if (M <= 64) return launch_dense_one<DT, 2, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, st);
-    return launch_dense_one<DT, 4, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, st);
+    return launch_dense_one<DT, 2, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, st);
 }
 
 // Host side, called by the C entry points for M <= SS_SKINNY_MAX_M.  Arguments are already validated.

@@ -68,7 +68,7 @@ __device__ inline uint32_t pack_bf16x2(float a, float b)
 }
 
 // Kernels for few tokens (gemm_skinny.hip): one workgroup per 32..128 output channels streams their weights once.
-constexpr int64_t SS_SKINNY_MAX_M = 128;
+constexpr int64_t SS_SKINNY_MAX_M = 64;
 ss_status launch_sparse_skinny(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
                                int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, hipStream_t stream);
 ss_status launch_dense_skinny(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, ss_dtype dtype,
