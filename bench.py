@@ -56,6 +56,9 @@ def parse():
                     help="instead of the headline step, time one of the other benchmark configurations and print its table "
                          "as one JSON line: dtypes_m = INT8/FP8/BF16 at M in {1,16,128,8192} on the Qwen2.5-7B shapes; "
                          "mid_m = INT8 at M in {64..2048}; patterns = 4:6, 6:8, 8:10 at M=8192 INT8; llama_block = Llama-3-8B linears at M=4096, 6:8 INT8")
+    ap.add_argument("--graph", action="store_true",
+                    help="sweeps only: time replays of a HIP graph holding the launches instead of eager calls from Python (below "
+                         "about 10 us per kernel the binding's call overhead is otherwise part of the figure)")
     ap.add_argument("--cpu-sample-tokens", type=int, default=4096)
     ap.add_argument("--cpu-sample-channels", type=int, default=8192)
     return ap.parse_args()
@@ -126,10 +129,21 @@ def sweep(args, torch, binding, synth, dev):
             for _ in range(args.warmup):
                 fn()
             e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            e0.record()
-            for _ in range(args.steps):
-                fn()
-            e1.record()
+            if args.graph:
+                torch.cuda.synchronize()
+                g = torch.cuda.CUDAGraph()
+                with torch.cuda.graph(g):
+                    for _ in range(args.steps):
+                        fn()
+                g.replay()
+                e0.record()
+                g.replay()
+                e1.record()
+            else:
+                e0.record()
+                for _ in range(args.steps):
+                    fn()
+                e1.record()
             torch.cuda.synchronize()
             t[k] = e0.elapsed_time(e1) / args.steps
         b = esize[dt]
@@ -142,7 +156,7 @@ def sweep(args, torch, binding, synth, dev):
                      "sparse_gemm_algorithmic_GBps": sparse_bytes / (t["sparse"] * 1e-3) * 1e-9,
                      "workspace_MiB": [ws_bytes[0] / 2 ** 20, ws_bytes[1] / 2 ** 20]})
         del X, Wq, w_vals, w_meta, XL, Xq, Y
-    print(json.dumps({"sweep": args.sweep, "steps": args.steps, "warmup": args.warmup, "speedup_bound": "N/(N-1)", "cases": rows}))
+    print(json.dumps({"sweep": args.sweep, "timing": "hip graph replay" if args.graph else "eager launches", "steps": args.steps, "warmup": args.warmup, "speedup_bound": "N/(N-1)", "cases": rows}))
 
 
 def main():
