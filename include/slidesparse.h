@@ -143,9 +143,9 @@ ss_status dense_gemm(const void* Xq, const float* s_x, const void* Wq, const flo
 
 /* The same two GEMMs with a caller-owned scratch buffer (Sec. 5 measures from decode, M = 64, to
  * prefill; small M leaves most of the chip idle unless the k range is split).  With a workspace of
- * at least slide_gemm_workspace_bytes() the 128 x 128-tile kernels split the k range of a tile
- * over several workgroups, write fp32 / int32 partial sums to the workspace and add them in a
- * fixed order in a second kernel (bit-reproducible; INT8 results are identical to the calls
+ * at least slide_gemm_workspace_bytes() the 128 x 128-tile kernels (and the few-token kernels on
+ * long rows) split the k range of a tile over several workgroups, write fp32 / int32 partial
+ * sums to the workspace and add them in a fixed order in a second kernel (bit-reproducible; INT8 results are identical to the calls
  * without workspace).  workspace: device memory, 16-byte aligned (SS_ERR_WORKSPACE otherwise),
  * contents irrelevant before and undefined after; NULL with workspace_bytes = 0, or a smaller
  * buffer, is allowed and gives fewer or no splits.  Calls that share one workspace must be ordered

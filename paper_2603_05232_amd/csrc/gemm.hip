@@ -624,7 +624,8 @@ extern "C" size_t slide_gemm_workspace_bytes(int64_t M, int64_t O, int64_t K, ss
     if (!valid_dtype(dtype) || M <= 0 || O <= 0 || K <= 0 || (K * elem_size(dtype)) % KSTEP != 0) return 0;
     const int64_t units = K * elem_size(dtype) / KSTEP;
     const ss_plan p = plan_gemm(M, O, units, (size_t)-1);
-    return p.path == SS_PATH_MID ? mid_workspace_bytes(M, O, p.S) : 0;
+    if (p.path == SS_PATH_MID) return mid_workspace_bytes(M, O, p.S);
+    return p.path == SS_PATH_SKINNY ? skinny_workspace_bytes(M, O, p.S) : 0;
 }
 
 extern "C" ss_status dense_gemm_ws(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t K,
@@ -636,7 +637,7 @@ extern "C" ss_status dense_gemm_ws(const void* Xq, const float* s_x, const void*
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const int64_t Kb = K * elem_size(dtype);
     const ss_plan p = plan_gemm(M, O, Kb / KSTEP, workspace_bytes);
-    if (p.path == SS_PATH_SKINNY) return launch_dense_skinny(Xq, s_x, Wq, s_w, M, O, Kb, dtype, Y, ldy, hs);
+    if (p.path == SS_PATH_SKINNY) return launch_dense_skinny(Xq, s_x, Wq, s_w, M, O, Kb, dtype, Y, ldy, workspace, p.S, hs);
     if (p.path == SS_PATH_MID) return launch_dense_mid(Xq, s_x, Wq, s_w, M, O, Kb, dtype, Y, ldy, workspace, p.S, hs);
     return launch_dense_tile(Xq, s_x, Wq, s_w, M, O, Kb, dtype, Y, ldy, hs);
 }
@@ -659,7 +660,7 @@ extern "C" ss_status slide_sparse_gemm_ws(const void* X_lifted, const float* s_x
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const int64_t Kpb = K_lifted * elem_size(dtype);
     const ss_plan p = plan_gemm(M, O, Kpb / KSTEP, workspace_bytes);
-    if (p.path == SS_PATH_SKINNY) return launch_sparse_skinny(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, hs);
+    if (p.path == SS_PATH_SKINNY) return launch_sparse_skinny(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, workspace, p.S, hs);
     if (p.path == SS_PATH_MID) return launch_sparse_mid(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, workspace, p.S, hs);
     return launch_sparse_tile(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, hs);
 }

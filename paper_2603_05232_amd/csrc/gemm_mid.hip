@@ -58,35 +58,6 @@ struct MidRowLoader {
     }
 };
 
-// One accumulator block: a[r] is channel o_lane + r (16 consecutive channels) of token tok.
-template <bool SCALED, typename ACC>
-__device__ inline void mid_store_block(const ACC& a, const float* __restrict__ s_x, const float* __restrict__ s_w, uint16_t* __restrict__ Y,
-                                       int64_t ldy, int64_t M, int64_t O, int64_t o_lane, int64_t tok)
-{
-    if (tok >= M || o_lane >= O) return;
-    uint32_t w[8];
-    if constexpr (SCALED) {
-        const float sx = s_x[tok];
-#pragma unroll
-        for (int q = 0; q < 8; ++q) {
-            const int64_t o0 = o_lane + 2 * q, o1 = o0 + 1;
-            w[q] = pack_bf16x2(((float)a[2 * q] * sx) * s_w[o0 < O ? o0 : O - 1], ((float)a[2 * q + 1] * sx) * s_w[o1 < O ? o1 : O - 1]);
-        }
-    } else {
-#pragma unroll
-        for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2((float)a[2 * q], (float)a[2 * q + 1]);
-    }
-    uint16_t* dst = Y + tok * ldy + o_lane;
-    if (((ldy & 7) == 0) && (((uintptr_t)Y & 15) == 0) && o_lane + 16 <= O) {
-        reinterpret_cast<uint4*>(dst)[0] = make_uint4(w[0], w[1], w[2], w[3]);
-        reinterpret_cast<uint4*>(dst)[1] = make_uint4(w[4], w[5], w[6], w[7]);
-    } else {
-#pragma unroll
-        for (int e = 0; e < 16; ++e)
-            if (o_lane + e < O) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-    }
-}
-
 // acc[f][tb][r] of lane (n = lane & 31, h = lane >> 5) is channel o_wave + 64 h + 16 f + r of token t_wave + 32 tb + n
 template <bool SCALED, typename ACC>
 __device__ inline void mid_store(const ACC (&acc)[2][2], const float* __restrict__ s_x, const float* __restrict__ s_w, uint16_t* __restrict__ Y,
@@ -97,7 +68,7 @@ __device__ inline void mid_store(const ACC (&acc)[2][2], const float* __restrict
     for (int f = 0; f < 2; ++f)
 #pragma unroll
         for (int tb = 0; tb < 2; ++tb)
-            mid_store_block<SCALED>(acc[f][tb], s_x, s_w, Y, ldy, M, O, o_wave + 64 * h + 16 * f, t_wave + tb * 32 + n);
+            store_block16<SCALED>(acc[f][tb], s_x, s_w, Y, ldy, M, O, o_wave + 64 * h + 16 * f, t_wave + tb * 32 + n);
 }
 
 // Split k: the raw accumulators of k-range s of tile `tile` go to the workspace as
@@ -162,7 +133,7 @@ __global__ __launch_bounds__(MD_THREADS) void k_mid_reduce(const v4i* __restrict
         }
     }
     const int64_t panel = tile / tiles_t, t0 = (tile - panel * tiles_t) * MD_TILE;
-    mid_store_block<MM::SCALED>(a, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo + 64 * (lane >> 5) + 16 * f, t0 + wt * 64 + tb * 32 + (lane & 31));
+    store_block16<MM::SCALED>(a, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo + 64 * (lane >> 5) + 16 * f, t0 + wt * 64 + tb * 32 + (lane & 31));
 }
 
 template <typename ACC> __device__ inline void mid_zero(ACC (&acc)[2][2])

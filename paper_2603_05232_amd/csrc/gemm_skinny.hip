@@ -92,6 +92,22 @@ __device__ inline void sk_store(const ACC (&acc)[TB], const float* __restrict__ 
     }
 }
 
+// Split k: the raw accumulators of k range blockIdx.y of workgroup blockIdx.x go to the workspace as
+// ws[range][workgroup][accumulator][register quad][lane] 16-byte groups.
+template <typename ACC, int NACC>
+__device__ inline void sk_store_partial(const ACC (&acc)[NACC], void* ws, int lane)
+{
+    typedef decltype(acc[0][0] + acc[0][0]) elem_t;
+    v4i* dst = static_cast<v4i*>(ws) + (((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * NACC * 4) * 64 + lane;
+#pragma unroll
+    for (int i = 0; i < NACC; ++i)
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const elem_t q[4] = {acc[i][4 * r4], acc[i][4 * r4 + 1], acc[i][4 * r4 + 2], acc[i][4 * r4 + 3]};
+            dst[(i * 4 + r4) * 64] = __builtin_bit_cast(v4i, q);
+        }
+}
+
 // ---- sparse ---------------------------------------------------------------------------------------------
 // Operands of one unit (two steps of 64 lifted bytes) of one wavefront.
 template <int TB, int FPW> struct SkSparseUnit { v4i a[2][FPW]; int idx[2][FPW]; v4i b[TB][4]; };
@@ -100,7 +116,7 @@ template <int DT, int TB, int FPW, int SK_WAVES>
 __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* __restrict__ XL, const float* __restrict__ s_x,
                                                                const uint8_t* __restrict__ w_vals, const uint8_t* __restrict__ w_meta,
                                                                const float* __restrict__ s_w, int64_t M, int64_t O, int64_t Kpb,
-                                                               uint16_t* __restrict__ Y, int64_t ldy)
+                                                               uint16_t* __restrict__ Y, int64_t ldy, void* __restrict__ ws)
 {
     typedef Mma<DT> MM;
     typedef int idx_t __attribute__((ext_vector_type(FPW)));
@@ -145,10 +161,12 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
 #pragma unroll
     for (int i = 0; i < FPW * TB; ++i) sk_zero(acc[i]);
     SkSparseUnit<TB, FPW> cur, nxt;
-    int u = wave;
-    if (u < U) load(cur, u);
-    for (; u < U; u += SK_WAVES) {
-        const bool more = u + SK_WAVES < U;
+    // k range of this workgroup: units [u, u_end) of U; gridDim.y ranges
+    const int u_end = (int)((int64_t)(blockIdx.y + 1) * U / gridDim.y);
+    int u = (int)((int64_t)blockIdx.y * U / gridDim.y) + wave;
+    if (u < u_end) load(cur, u);
+    for (; u < u_end; u += SK_WAVES) {
+        const bool more = u + SK_WAVES < u_end;
         if (more) load(nxt, u + SK_WAVES);
 #pragma unroll
         for (int h = 0; h < 2; ++h)
@@ -163,6 +181,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
     }
     sk_reduce<SK_WAVES, typename MM::acc_t, FPW * TB>(acc, red, wave, lane);
     if (wave == 0) {
+        if (gridDim.y > 1) { sk_store_partial<typename MM::acc_t, FPW * TB>(acc, ws, lane); return; }
 #pragma unroll
         for (int f = 0; f < FPW; ++f) {
             typename MM::acc_t part[TB];
@@ -183,7 +202,7 @@ template <int TB, int FPW> struct SkDenseUnit { v4i a[FPW][4]; v4i b[TB][4]; };
 template <int DT, int TB, int FPW, int SK_WAVES>
 __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* __restrict__ Xq, const float* __restrict__ s_x,
                                                               const uint8_t* __restrict__ Wq, const float* __restrict__ s_w, int64_t M,
-                                                              int64_t O, int64_t Kb, uint16_t* __restrict__ Y, int64_t ldy)
+                                                              int64_t O, int64_t Kb, uint16_t* __restrict__ Y, int64_t ldy, void* __restrict__ ws)
 {
     typedef Mma<DT> MM;
     typedef typename MM::dfrag_t frag_t;
@@ -235,10 +254,11 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* _
     for (int i = 0; i < FPW * TB; ++i) sk_zero(acc[i]);
     SkDenseUnit<TB, FPW> cur, nxt;
     uint8_t* my = tile[wave];
-    int u = wave;
-    if (u < U) load(cur, u);
-    for (; u < U; u += SK_WAVES) {
-        const bool more = u + SK_WAVES < U;
+    const int u_end = (int)((int64_t)(blockIdx.y + 1) * U / gridDim.y);
+    int u = (int)((int64_t)blockIdx.y * U / gridDim.y) + wave;
+    if (u < u_end) load(cur, u);
+    for (; u < u_end; u += SK_WAVES) {
+        const bool more = u + SK_WAVES < u_end;
         if (more) load(nxt, u + SK_WAVES);
         // lines -> wavefront-private LDS tile -> fragments (LDS operations of one wavefront execute in order)
 #pragma unroll
@@ -272,6 +292,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* _
     }
     sk_reduce<SK_WAVES, typename MM::acc_t, FPW * TB>(acc, red, wave, lane);
     if (wave == 0) {
+        if (gridDim.y > 1) { sk_store_partial<typename MM::acc_t, FPW * TB>(acc, ws, lane); return; }
 #pragma unroll
         for (int f = 0; f < FPW; ++f) {
             typename MM::acc_t part[TB];
@@ -280,6 +301,35 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* _
             sk_store<MM::SCALED, typename MM::acc_t, TB>(part, s_x, s_w, Y, ldy, M, O, o0 + 32 * f + 16 * (lane >> 5), lane);
         }
     }
+}
+
+// Split k (single-fragment workgroups only): sum of the S partial accumulators of fragment blockIdx.x in range order
+// and the scale epilogue; thread (tb, lane) owns one block.  PANEL_ORDER: fragment F is fragment F % 4 of weight panel
+// F / 4 (channels panel * 128 + 64 h + 16 (F % 4) + r); otherwise it is channels 32 F + 16 h + r.
+template <int DT, int TB, bool PANEL_ORDER>
+__global__ __launch_bounds__(64 * TB) void k_skinny_reduce(const v4i* __restrict__ ws, int S, const float* __restrict__ s_x,
+                                                          const float* __restrict__ s_w, int64_t M, int64_t O, uint16_t* __restrict__ Y, int64_t ldy)
+{
+    typedef Mma<DT> MM;
+    typedef typename MM::acc_t acc_t;
+    typedef decltype(acc_t{}[0] + acc_t{}[0]) elem_t;
+    typedef elem_t quad_t __attribute__((ext_vector_type(4)));
+    const int64_t F = blockIdx.x, nfrag = gridDim.x;
+    const int tb = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
+    acc_t a;
+#pragma unroll
+    for (int r = 0; r < 16; ++r) a[r] = 0;
+    for (int s = 0; s < S; ++s) {
+        const v4i* src = ws + (((s * nfrag + F) * TB + tb) * 4) * 64 + lane;
+#pragma unroll
+        for (int r4 = 0; r4 < 4; ++r4) {
+            const quad_t q = __builtin_bit_cast(quad_t, src[r4 * 64]);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) a[4 * r4 + e] += q[e];
+        }
+    }
+    const int64_t o_lane = PANEL_ORDER ? (F >> 2) * PANEL + 64 * h + 16 * (F & 3) : F * 32 + 16 * h;
+    store_block16<MM::SCALED>(a, s_x, s_w, Y, ldy, M, O, o_lane, tb * 32 + (lane & 31));
 }
 
 }  // namespace ss
@@ -297,41 +347,48 @@ static int pick_fpw(int64_t frags)
 
 template <int DT, int TB, int FPW>
 static ss_status launch_sparse_one(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
-                                   int64_t Kpb, void* Y, int64_t ldy, hipStream_t stream)
+                                   int64_t Kpb, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream)
 {
     const int64_t npanels = (O + PANEL - 1) / PANEL;
     const unsigned grid = (unsigned)(npanels * (FRAGS_PER_PANEL / FPW));
-    if (FPW == 1 && TB <= 2 && (int)grid < cu_count())
-        hipLaunchKernelGGL((k_sparse_skinny<DT, TB, 1, 8>), dim3(grid), dim3(512), 0, stream, static_cast<const uint8_t*>(XL), s_x,
-                           static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy);
-    else
+    if (FPW == 1 && (int)grid < cu_count()) {
+        hipLaunchKernelGGL((k_sparse_skinny<DT, TB, 1, 8>), dim3(grid, (unsigned)S), dim3(512), 0, stream, static_cast<const uint8_t*>(XL), s_x,
+                           static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy, ws);
+        if (S > 1 && launch_status() == SS_OK)
+            hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
+                               static_cast<uint16_t*>(Y), ldy);
+    } else
         hipLaunchKernelGGL((k_sparse_skinny<DT, TB, FPW, 4>), dim3(grid), dim3(256), 0, stream, static_cast<const uint8_t*>(XL), s_x,
-                           static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy);
+                           static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy, ws);
     return launch_status();
 }
 
 template <int DT, int TB, int FPW>
 static ss_status launch_dense_one(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, void* Y,
-                                  int64_t ldy, hipStream_t stream)
+                                  int64_t ldy, void* ws, int S, hipStream_t stream)
 {
     const unsigned grid = (unsigned)((O + 32 * FPW - 1) / (32 * FPW));
-    if (FPW == 1 && TB <= 2 && (int)grid < cu_count())
-        hipLaunchKernelGGL((k_dense_skinny<DT, TB, 1, 8>), dim3(grid), dim3(512), 0, stream, static_cast<const uint8_t*>(Xq), s_x,
-                           static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy);
-    else
+    if (FPW == 1 && (int)grid < cu_count()) {
+        hipLaunchKernelGGL((k_dense_skinny<DT, TB, 1, 8>), dim3(grid, (unsigned)S), dim3(512), 0, stream, static_cast<const uint8_t*>(Xq), s_x,
+                           static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, ws);
+        if (S > 1 && launch_status() == SS_OK)
+            hipLaunchKernelGGL((k_skinny_reduce<DT, TB, false>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
+                               static_cast<uint16_t*>(Y), ldy);
+    } else
         hipLaunchKernelGGL((k_dense_skinny<DT, TB, FPW, 4>), dim3(grid), dim3(256), 0, stream, static_cast<const uint8_t*>(Xq), s_x,
-                           static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy);
+                           static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, ws);
     return launch_status();
 }
 
-// token blocks of 32: 1 (M <= 32) or 2 (M <= 64)
+// token blocks of 32: 1 (M <= 32) or 2 (M <= 64).  S > 1 only arrives where skinny_splits() allows it: fewer fragments
+// than compute units, hence single-fragment workgroups of eight wavefronts.
 template <int DT>
 static ss_status launch_sparse_dt(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
-                                  int64_t Kpb, void* Y, int64_t ldy, hipStream_t st)
+                                  int64_t Kpb, void* Y, int64_t ldy, void* ws, int S, hipStream_t st)
 {
     const int64_t frags = (O + PANEL - 1) / PANEL * FRAGS_PER_PANEL;
     const int fpw = pick_fpw(frags);
-#define SS_GO(TB, FPW) return launch_sparse_one<DT, TB, FPW>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, st)
+#define SS_GO(TB, FPW) return launch_sparse_one<DT, TB, FPW>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, FPW == 1 ? S : 1, st)
     if (M <= 32) { if (fpw == 4) SS_GO(1, 4); if (fpw == 2) SS_GO(1, 2); SS_GO(1, 1); }
     if (fpw == 4) SS_GO(2, 4);
     if (fpw == 2) SS_GO(2, 2);
@@ -341,37 +398,61 @@ static ss_status launch_sparse_dt(const void* XL, const float* s_x, const void* 
 
 template <int DT>
 static ss_status launch_dense_dt(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, void* Y,
-                                 int64_t ldy, hipStream_t st)
+                                 int64_t ldy, void* ws, int S, hipStream_t st)
 {
     // One fragment per workgroup: the dense kernel stages its weight lines through LDS, and more fragments per
     // workgroup cost more in occupancy than they save in token re-reads (measured: 21 vs 35 us on 3584 -> 37888).
-    if (M <= 32) return launch_dense_one<DT, 1, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, st);
-    return launch_dense_one<DT, 2, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, st);
+    if (M <= 32) return launch_dense_one<DT, 1, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, st);
+    return launch_dense_one<DT, 2, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, st);
 }
 
 // Host side, called by the C entry points for M <= SS_SKINNY_MAX_M.  Arguments are already validated.
 namespace ss {
 
+// Number of k ranges for the few-token kernels: only where the 32-channel fragments (counted in whole panels, as
+// the sparse kernel launches them) are fewer than the compute units, so that workgroups are single fragments of
+// eight wavefronts; every wavefront keeps at least eight units; no more than the workspace holds.  Measured on
+// 18944 -> 3584 (112 fragments, INT8 6:8): M = 16 28 -> 20 us, M = 32 37 -> 24 us; at M = 1 the second kernel
+// costs what the split saves (19 us either way), so fewer than 8 tokens are not split.
+int skinny_splits(int64_t M, int64_t O, int64_t units, size_t ws_bytes)
+{
+    const int64_t nfrag = (O + PANEL - 1) / PANEL * FRAGS_PER_PANEL;
+    const int cus = cu_count();
+    if (M < 8 || M > SS_SKINNY_MAX_M || nfrag >= cus) return 1;
+    int64_t S = cus / nfrag;
+    if (S > units / 64) S = units / 64;
+    const int64_t fit = (int64_t)(ws_bytes / skinny_workspace_bytes(M, O, 2) * 2);
+    if (S > fit) S = fit;
+    return S < 2 ? 1 : (int)S;
+}
+
+size_t skinny_workspace_bytes(int64_t M, int64_t O, int S)
+{
+    const int64_t nfrag = (O + PANEL - 1) / PANEL * FRAGS_PER_PANEL;
+    const int tb = M <= 32 ? 1 : 2;
+    return S > 1 ? (size_t)S * nfrag * tb * 16 * 64 * 4 : 0;
+}
+
 ss_status launch_sparse_skinny(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
-                               int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, hipStream_t stream)
+                               int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream)
 {
     switch (dtype) {
-    case SS_I8: return launch_sparse_dt<SS_I8>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, stream);
-    case SS_FP8_E4M3: return launch_sparse_dt<SS_FP8_E4M3>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, stream);
-    case SS_BF16: return launch_sparse_dt<SS_BF16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, stream);
-    case SS_FP16: return launch_sparse_dt<SS_FP16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, stream);
+    case SS_I8: return launch_sparse_dt<SS_I8>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
+    case SS_FP8_E4M3: return launch_sparse_dt<SS_FP8_E4M3>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
+    case SS_BF16: return launch_sparse_dt<SS_BF16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
+    case SS_FP16: return launch_sparse_dt<SS_FP16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
     }
     return SS_ERR_DTYPE;
 }
 
 ss_status launch_dense_skinny(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, ss_dtype dtype,
-                              void* Y, int64_t ldy, hipStream_t stream)
+                              void* Y, int64_t ldy, void* ws, int S, hipStream_t stream)
 {
     switch (dtype) {
-    case SS_I8: return launch_dense_dt<SS_I8>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, stream);
-    case SS_FP8_E4M3: return launch_dense_dt<SS_FP8_E4M3>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, stream);
-    case SS_BF16: return launch_dense_dt<SS_BF16>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, stream);
-    case SS_FP16: return launch_dense_dt<SS_FP16>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, stream);
+    case SS_I8: return launch_dense_dt<SS_I8>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, stream);
+    case SS_FP8_E4M3: return launch_dense_dt<SS_FP8_E4M3>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, stream);
+    case SS_BF16: return launch_dense_dt<SS_BF16>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, stream);
+    case SS_FP16: return launch_dense_dt<SS_FP16>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, stream);
     }
     return SS_ERR_DTYPE;
 }

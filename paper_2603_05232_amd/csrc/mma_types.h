@@ -67,12 +67,47 @@ __device__ inline uint32_t pack_bf16x2(float a, float b)
     return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2));
 }
 
+// Epilogue of one accumulator block held by one lane: a[r] is channel o_lane + r (16 consecutive channels) of token
+// tok; Y = bf16((float(a) * s_x[tok]) * s_w[o]) (SCALED) or bf16(a).  Out-of-range tokens and channels are skipped.
+template <bool SCALED, typename ACC>
+__device__ inline void store_block16(const ACC& a, const float* __restrict__ s_x, const float* __restrict__ s_w, uint16_t* __restrict__ Y,
+                                     int64_t ldy, int64_t M, int64_t O, int64_t o_lane, int64_t tok)
+{
+    if (tok >= M || o_lane >= O) return;
+    uint32_t w[8];
+    if constexpr (SCALED) {
+        const float sx = s_x[tok];
+#pragma unroll
+        for (int q = 0; q < 8; ++q) {
+            const int64_t o0 = o_lane + 2 * q, o1 = o0 + 1;
+            w[q] = pack_bf16x2(((float)a[2 * q] * sx) * s_w[o0 < O ? o0 : O - 1], ((float)a[2 * q + 1] * sx) * s_w[o1 < O ? o1 : O - 1]);
+        }
+    } else {
+#pragma unroll
+        for (int q = 0; q < 8; ++q) w[q] = pack_bf16x2((float)a[2 * q], (float)a[2 * q + 1]);
+    }
+    uint16_t* dst = Y + tok * ldy + o_lane;
+    if (((ldy & 7) == 0) && (((uintptr_t)Y & 15) == 0) && o_lane + 16 <= O) {
+        reinterpret_cast<uint4*>(dst)[0] = make_uint4(w[0], w[1], w[2], w[3]);
+        reinterpret_cast<uint4*>(dst)[1] = make_uint4(w[4], w[5], w[6], w[7]);
+    } else {
+#pragma unroll
+        for (int e = 0; e < 16; ++e)
+            if (o_lane + e < O) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+    }
+}
+
 // Kernels for few tokens (gemm_skinny.hip): one workgroup per 32..128 output channels streams their weights once.
+// With S > 1 (only where every workgroup is a single 32-channel fragment and there are fewer of them than compute
+// units) the k range is split over S workgroups per fragment; partial sums go through `ws`
+// (skinny_workspace_bytes(M, O, S) bytes) and a second kernel adds them in a fixed order.
 constexpr int64_t SS_SKINNY_MAX_M = 64;
+int skinny_splits(int64_t M, int64_t O, int64_t units, size_t ws_bytes);
+size_t skinny_workspace_bytes(int64_t M, int64_t O, int S);
 ss_status launch_sparse_skinny(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
-                               int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, hipStream_t stream);
+                               int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
 ss_status launch_dense_skinny(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, ss_dtype dtype,
-                              void* Y, int64_t ldy, hipStream_t stream);
+                              void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
 
 
 // The 256 x 256 tile kernels (gemm.hip).
@@ -95,7 +130,9 @@ inline int64_t mid_tiles(int64_t M, int64_t O) { return ((O + 127) / 128) * ((M 
 
 // Which kernel family a GEMM of M tokens x O channels over `units` 128-byte k units runs on, and in how many k
 // ranges (S > 1 only for SS_PATH_MID and only with a workspace).  Measured on the Qwen2.5-7B shapes (INT8, 6:8):
-//   M <= 32                      few-token kernels (7 to 9 us on 3584 -> 4608, where the others need 15 and 31);
+//   M <= 32                      few-token kernels (7 to 9 us on 3584 -> 4608, where the others need 15 and 31), their k
+//                                range split in two or three where the fragments are fewer than the compute units and the
+//                                rows long (18944 -> 3584);
 //   32 < M <= 64                 the same, unless the rows are long and can be split (18944 -> 3584 at M = 48:
 //                                53 us few-token, 23 us in 8 ranges of 128 x 128 tiles);
 //   up to 320 tiles of 128 x 128 those tiles (M = 256 on 3584 -> 4608: 17 us in 3 ranges, 33 us with 256 x 256
@@ -105,10 +142,10 @@ enum ss_path { SS_PATH_SKINNY, SS_PATH_MID, SS_PATH_TILE };
 struct ss_plan { ss_path path; int S; };
 inline ss_plan plan_gemm(int64_t M, int64_t O, int64_t units, size_t ws_bytes)
 {
-    if (M <= 32) return {SS_PATH_SKINNY, 1};
+    if (M <= 32) return {SS_PATH_SKINNY, skinny_splits(M, O, units, ws_bytes)};
     if (M > 64 && mid_tiles(M, O) > 320) return {SS_PATH_TILE, 1};
     const int S = mid_splits(M, O, units, ws_bytes);
-    if (M <= 64 && !(S > 1 && units >= 96)) return {SS_PATH_SKINNY, 1};
+    if (M <= 64 && !(S > 1 && units >= 96)) return {SS_PATH_SKINNY, skinny_splits(M, O, units, ws_bytes)};
     return {SS_PATH_MID, S};
 }
 

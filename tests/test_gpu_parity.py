@@ -315,10 +315,12 @@ def _workspace(M, O, Kp, dtype, fill, scale=1.0):
                                      (4, 48, 200, 8192),        # 32 < M <= 64 with long rows
                                      (3, 300, 130, 3072),       # ragged tokens and channels, K' = 4096
                                      (2, 129, 257, 4096),       # native 2:4
-                                     (5, 64, 128, 10240)])      # K' = 16384
+                                     (5, 64, 128, 10240),       # K' = 16384
+                                     (5, 16, 200, 10240),       # few-token kernels, k range split in two
+                                     (4, 24, 130, 16384)])      # ... in three (K' = 24576)
 def test_gemm_split_k_with_workspace(dtype, N, M, O, K):
-    """The 128 x 128-tile kernels with the k range of a tile split over several workgroups: partial sums go
-    through the caller's workspace and are added in a fixed order.  INT8 must equal the oracle bit for bit (and
+    """The 128 x 128-tile kernels (and, for few tokens on long rows, the few-token kernels) with the k range split
+    over several workgroups: partial sums go through the caller's workspace and are added in a fixed order.  INT8 must equal the oracle bit for bit (and
     so the call without workspace); floats stay within the GEMM tolerance and are reproducible bit for bit."""
     X = synth.activations(M, K, seed=M + K, n_outliers=2)
     W = synth.weights(O, K, seed=O + N)
