@@ -215,8 +215,14 @@ def test_gemm_strided_output_and_random_sparse_weights():
 def _float_gemm_check(Ybits, ref, dtype):
     """Floating-point bar: max |Y - Y_ref| / (||Xd[m]||_2 ||Wd[o]||_2) <= 1e-2 with Xd, Wd the dequantised
     operands and Y_ref the fp64 result before the bf16 rounding.  On top of it a bound derived from the
-    arithmetic (fp32 accumulation over K terms + one bf16 rounding), which a misplaced operand cannot meet:
-    |Y - Y_ref| <= 2^-8 |Y_ref| + K 2^-23 ||Xd[m]|| ||Wd[o]||."""
+    arithmetic (fp32 accumulation over K terms + one bf16 rounding):
+    |Y - Y_ref| <= 2^-8 |Y_ref| + K 2^-23 ||Xd[m]|| ||Wd[o]||.
+    FP8 adds 2^-9 ||Xd[m]|| ||Wd[o]||: the fp8 matrix instructions of gfx950 (sparse and dense) add the products of
+    an instruction in small groups aligned to the group's largest product and keep 14 bits below it (measured: beside
+    a product of 2^8, products of 2^-6 in the same group of 8 are dropped, 2^-5 survive; bf16 products keep all 24
+    bits), so each product loses less than 2^-13 of its group's largest, and the group maxima sum to at most
+    sum |x w| <= ||x|| ||w||: at most 8 (16 allowed for) x 2^-13 of that in total.  Operand placement is pinned
+    separately by the exact small-integer cases, where every product survives."""
     Xd = so.to_real(ref["Xq"], dtype)
     Wd = so.to_real(ref["Wq"], dtype)
     if dtype not in ("bf16", "fp16"):
@@ -229,7 +235,8 @@ def _float_gemm_check(Ybits, ref, dtype):
     err = np.abs(Y - Yref)
     assert np.max(err / norm) <= 1e-2
     K = Xd.shape[1]
-    assert np.all(err <= 2.0 ** -8 * np.abs(Yref) + K * 2.0 ** -23 * norm + 1e-30)
+    group_truncation = 2.0 ** -9 if dtype == "fp8" else 0.0
+    assert np.all(err <= 2.0 ** -8 * np.abs(Yref) + (K * 2.0 ** -23 + group_truncation) * norm + 1e-30)
 
 
 @pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
@@ -406,7 +413,8 @@ def test_random_shapes_int8_end_to_end(N, M, O, K):
 
 
 @pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
-@pytest.mark.parametrize("N,M,O,K", _random_cases(8, seed=77) + _ragged_k_cases(6, seed=32))
+@pytest.mark.parametrize("N,M,O,K", _random_cases(8, seed=77) + _ragged_k_cases(6, seed=32) +
+                         [(4, 1100, 2100, 103)])         # short rows, many outputs that cancel to ~0: tightest for the derived bound
 def test_random_shapes_float_end_to_end(dtype, N, M, O, K):
     X = synth.activations(M, K, seed=M + O + K, n_outliers=2)
     W = synth.weights(O, K, seed=M + O + N)
