@@ -136,3 +136,33 @@ def test_longest_rows_int8(M, O):
         assert np.array_equal(bits16(binding.slide_sparse_gemm(XL, dev(s_x), w_vals, w_meta, dev(s_w), O, "i8", workspace=ws)), exp)
     if K % 128 == 0:
         assert np.array_equal(bits16(binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8")), exp)
+
+
+@pytest.mark.parametrize("M,ldy_log2", [(70000, 16), (300, 21), (20, 21)])
+def test_output_offsets_beyond_32_bits(M, ldy_log2):
+    """Y with a row stride so large that element offsets exceed 2^32 (M = 70000, ldy = 2^16: 256 x 256 tiles) or byte
+    offsets 2^31 (ldy = 2^21: 128 x 128 tiles and the few-token kernels): 64-bit addressing of the output, and nothing
+    is written outside the result columns."""
+    N, K, O = 4, 256, 64
+    ldy = 1 << ldy_log2
+    rng = np.random.default_rng(M)
+    Wq = rng.integers(-127, 128, size=(O, K), dtype=np.int8)
+    Wq.reshape(O, K // 8, 8)[:, :, [1, 6]] = 0
+    Xq = rng.integers(-127, 128, size=(M, K), dtype=np.int8)
+    s_x = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    s_w = rng.uniform(1e-4, 1e-3, O).astype(np.float32)
+    w_vals, w_meta = binding.slide_decompose(dev(Wq), N, "i8")
+    XL = dev(so.lift(Xq, N))
+    buf = torch.zeros((M, ldy), dtype=torch.bfloat16, device=XL.device)
+    assert buf.numel() > 2 ** 32 or M < 2048
+    binding.slide_sparse_gemm(XL, dev(s_x), w_vals, w_meta, dev(s_w), O, "i8", out=buf[:, :O])
+    rows = np.unique(np.concatenate([rng.choice(M, size=min(M, 64), replace=False), [0, M - 1]]))
+    exp = so.epilogue(so.gemm_exact(Xq[rows], Wq, "i8"), s_x[rows], s_w, "i8")
+    ri = torch.from_numpy(rows).to(buf.device)
+    assert np.array_equal(bits16(buf[ri][:, :O].contiguous()), exp)
+    assert not bool(buf[ri][:, O:O + 4096].any())                          # columns beside the result stay zero
+    total = buf[:, :O].float().abs().sum().item()
+    assert abs(buf.float().abs().sum().item() - total) <= 1e-3 * total     # nothing was written anywhere else
+    buf.zero_()
+    binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8", out=buf[:, :O])
+    assert np.array_equal(bits16(buf[ri][:, :O].contiguous()), exp)
