@@ -119,3 +119,20 @@ def test_argument_errors_return_codes(lib):
     assert lib.dense_gemm(None, None, None, None, 0, 128, 128, 0, None, 128, None) == 0
     assert binding.status_string(0) == "ok" and "N" in binding.status_string(2)
     assert lib.slide_format_version() >= 1
+
+
+def test_header_is_plain_c(tmp_path):
+    """The boundary is a C ABI: the header must compile as C99 on its own (no C++ or HIP types in it)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler")
+    src = tmp_path / "use_header.c"
+    src.write_text('#include "slidesparse.h"\n'
+                   'int main(void) { size_t v = 0, m = 0; ss_dtype d = SS_FP16; (void)d;\n'
+                   '  return (int)slide_packed_sizes(128, 512, 4, SS_I8, &v, &m) + (int)slide_lifted_ld(512, 4, SS_BF16) * 0; }\n')
+    inc = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include")
+    r = subprocess.run([gcc, "-std=c99", "-Wall", "-Werror", "-pedantic", "-fsyntax-only", "-I", inc, str(src)],
+                       stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True)
+    assert r.returncode == 0, r.stdout
