@@ -68,6 +68,71 @@ __global__ __launch_bounds__(256) void k_decompose_canonical(const typename Elem
     if (violations && nnz > 2 * N - 2) atomicAdd(violations, 1);
 }
 
+// One 2N block of a row with its decomposition: the block's elements (zero beyond the row), the positions each of
+// its N-1 windows takes (Alg. 2, greedy in window order) and its non-zero count.  Loading and decomposing a block once
+// and reading several windows from it is what the packed kernel does: a lane's windows come in runs of consecutive
+// windows, so it touches two to four blocks instead of re-reading one per window.
+template <int ES> struct SlideBlock {
+    typedef typename Elem<ES>::T T;
+    T v[16];
+    uint32_t taken[7];                                   // per window: 4-bit mask of the offsets it stores
+    int nnz;
+
+    __device__ void load(const T* row, int K, int N, int g, bool fp)
+    {
+        const T* blk = row + (int64_t)g * 2 * N;
+        const int left = K - g * 2 * N;                  // elements of this block inside the row (<= 0: none)
+        constexpr int PER = 4 / ES;                      // elements per 32-bit word
+        if (left >= 2 * N && (((uintptr_t)blk) & 3) == 0 && ((2 * N) % PER) == 0) {
+            const uint32_t* w = reinterpret_cast<const uint32_t*>(blk);
+#pragma unroll
+            for (int i = 0; i < 16 / PER; ++i) {
+                const uint32_t x = i * PER < 2 * N ? w[i] : 0u;
+#pragma unroll
+                for (int e = 0; e < PER; ++e) v[i * PER + e] = (T)(x >> (8 * ES * e));
+            }
+        } else {
+#pragma unroll
+            for (int p = 0; p < 16; ++p) v[p] = (p < 2 * N && p < left) ? blk[p] : (T)0;
+        }
+        uint32_t nzmask = 0;
+#pragma unroll
+        for (int p = 0; p < 16; ++p) nzmask |= (uint32_t)(p < 2 * N && Elem<ES>::nz(v[p], fp)) << p;
+        nnz = __popc(nzmask);
+        uint32_t used = 0;
+#pragma unroll
+        for (int w = 0; w < 7; ++w) {                    // windows in ascending order; each takes its first <= 2 unused non-zeros
+            uint32_t t = 0;
+            int cnt = 0;
+#pragma unroll
+            for (int d = 0; d < 4; ++d) {
+                const int p = 2 * w + d;
+                if (w < N - 1 && ((nzmask >> p) & 1u) && !((used >> p) & 1u) && cnt < 2) { used |= 1u << p; t |= 1u << d; ++cnt; }
+            }
+            taken[w] = t;
+        }
+    }
+
+    // window l: stored values and their positions i0 < i1 (padded with the lowest offsets that hold no stored non-zero)
+    __device__ void window(int l, T& v0, T& v1, uint32_t& i0, uint32_t& i1) const
+    {
+        uint32_t t = 0;
+#pragma unroll
+        for (int w = 0; w < 7; ++w) t = w == l ? taken[w] : t;
+        uint32_t chosen = t;
+#pragma unroll
+        for (int d = 0; d < 4; ++d) if (__popc(chosen) < 2) chosen |= 1u << d;
+        i0 = __ffs(chosen) - 1;
+        i1 = 31 - __clz(chosen);
+        const int p0 = 2 * l + (int)i0, p1 = 2 * l + (int)i1;
+        T e0 = 0, e1 = 0;
+#pragma unroll
+        for (int p = 0; p < 16; ++p) { e0 = p == p0 ? v[p] : e0; e1 = p == p1 ? v[p] : e1; }
+        v0 = ((t >> i0) & 1u) ? e0 : (T)0;
+        v1 = ((t >> i1) & 1u) ? e1 : (T)0;
+    }
+};
+
 // packed form: one thread per (panel, 64-byte step, fragment, lane)
 template <int ES>
 __global__ __launch_bounds__(256) void k_decompose_packed(const typename Elem<ES>::T* __restrict__ Wq, int64_t O, int K, int N, bool fp,
@@ -90,16 +155,23 @@ __global__ __launch_bounds__(256) void k_decompose_packed(const typename Elem<ES
     if (o < O) {
         m = 0;
         int bad = 0;
+        SlideBlock<ES> B;
+        int g_held = -1;
+        const T* row = Wq + o * (int64_t)K;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
             const int j = step * (2 * NW) + step_window<ES>(qa, w);
             const int g = j / (N - 1), l = j - g * (N - 1);
-            T v0, v1; uint32_t i0, i1; int nnz;
-            slide_window<ES>(Wq + o * (int64_t)K, K, N, g, l, fp, v0, v1, i0, i1, nnz);
+            if (g != g_held) {                           // a lane's windows ascend, so every block is loaded once
+                B.load(row, K, N, g, fp);
+                g_held = g;
+            }
+            T v0, v1; uint32_t i0, i1;
+            B.window(l, v0, v1, i0, i1);
             if constexpr (ES == 1) v[w >> 1] |= ((uint32_t)v0 | ((uint32_t)v1 << 8)) << (16 * (w & 1));
             else v[w] = (uint32_t)v0 | ((uint32_t)v1 << 16);
             m |= (i0 | (i1 << 2)) << (4 * w);
-            bad += nnz > 2 * N - 2;
+            bad += (l == 0 && B.nnz > 2 * N - 2);       // pattern check, counted by the lane that holds the block's first window
         }
         if (violations && bad) atomicAdd(violations, bad);
     }
