@@ -114,6 +114,19 @@ def test_prune_quant(dtype, N, O, K):
         assert np.array_equal(host(gs), exps)
 
 
+@pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
+@pytest.mark.parametrize("N,O,K", [(4, 33, 512), (3, 7, 100), (8, 5, 1000)])
+def test_prune_quant_bf16_weights(dtype, N, O, K):
+    """Weights handed over as bf16 (in_dtype = SS_IN_BF16): the oracle sees their exact fp32 values."""
+    Wb = so.bf16_bits(synth.weights(O, K, seed=20 + N))
+    Wb[0, : min(K, 2 * N)] = 0x3F00                          # ties (0.5): the lower indices survive
+    expq, exps = so.prepare_weights(so.bf16_to_f32(Wb), N, dtype)
+    gq, gs = binding.slide_prune_quant(dev(Wb.view(np.int16)).view(torch.bfloat16), N, dtype)
+    assert np.array_equal(from_dev_q(gq, dtype), expq)
+    if dtype not in ("bf16", "fp16"):
+        assert np.array_equal(host(gs), exps)
+
+
 # ------------------------------------------------------------------ slide_decompose (canonical form)
 @pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("N,O,K", [(4, 512, 512), (2, 5, 64), (3, 33, 6 * 21), (5, 7, 200), (6, 3, 120), (7, 2, 14 * 5), (8, 4, 160),
