@@ -163,6 +163,15 @@ def test_decompose_counts_pattern_violations():
     Wq[3, 16:22] = 3                                         # 6: allowed
     _, _, viol = binding.slide_decompose_canonical(dev(Wq), N, "i8")
     assert int(host(viol)[0]) == 2
+    _, _, viol_packed = binding.slide_decompose(dev(Wq), N, "i8", count_violations=True)
+    assert int(host(viol_packed)[0]) == 2                    # the packed form counts the same blocks, once each
+    Wh = np.zeros((3, 24), dtype=np.uint16)                  # 16-bit elements, 4:6, row length not a multiple of 128 bytes
+    Wh[0, 0:5] = 0x3C00                                      # 5 non-zeros in a block of 6
+    Wh[1, 6:10] = 0x3C00                                     # 4: allowed
+    Wh[2, 18:24] = 0xBC00                                    # 6 non-zeros
+    Wh[2, 3] = 0x8000                                        # -0 is not a non-zero
+    _, _, v16 = binding.slide_decompose(to_dev_q(Wh, "fp16"), 3, "fp16", count_violations=True)
+    assert int(host(v16)[0]) == 2
 
 
 # ------------------------------------------------------------------ GEMMs
