@@ -136,6 +136,15 @@ __global__ __launch_bounds__(MD_THREADS) void k_mid_reduce(const v4i* __restrict
     store_block16<MM::SCALED>(a, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo + 64 * (lane >> 5) + 16 * f, t0 + wt * 64 + tb * 32 + (lane & 31));
 }
 
+// Tile of this workgroup.  Workgroup ids go round-robin over the 8 XCDs; when the tile count allows, the tiles are
+// renumbered so that every XCD works on one contiguous run of tiles: the token tiles of a weight panel (consecutive
+// tile numbers) then share that panel's weights in one L2 instead of fetching them once per XCD.
+__device__ inline int mid_tile_of_block()
+{
+    const int nt = gridDim.x, b = blockIdx.x;
+    return (nt & 7) == 0 ? (b & 7) * (nt >> 3) + (b >> 3) : b;
+}
+
 template <typename ACC> __device__ inline void mid_zero(ACC (&acc)[2][2])
 {
 #pragma unroll
@@ -161,8 +170,9 @@ __global__ __launch_bounds__(MD_THREADS) void k_sparse_mid(const uint8_t* __rest
     const int U_all = (int)(Kpb / (2 * FRAG_KB));
     // k range of this workgroup: units [u0, u0 + U); gridDim.y ranges, all non-empty (gridDim.y <= U_all)
     const int u0 = (int)((int64_t)blockIdx.y * U_all / gridDim.y), U = (int)((int64_t)(blockIdx.y + 1) * U_all / gridDim.y) - u0;
-    const int64_t panel = blockIdx.x / tiles_t;
-    const int64_t t0 = (int64_t)(blockIdx.x - panel * tiles_t) * MD_TILE;
+    const int tile = mid_tile_of_block();
+    const int64_t panel = tile / tiles_t;
+    const int64_t t0 = (int64_t)(tile - panel * tiles_t) * MD_TILE;
 
     MidRowLoader lb;
     lb.init(XL + (int64_t)u0 * ROWB, Kpb, t0, M, wave, lane);
@@ -214,7 +224,7 @@ __global__ __launch_bounds__(MD_THREADS) void k_sparse_mid(const uint8_t* __rest
         slot = slot == MD_S_RING - 1 ? 0 : slot + 1;
         lslot = lslot == MD_S_RING - 1 ? 0 : lslot + 1;
     }
-    if (gridDim.y > 1) mid_store_partial(acc, ws, (int64_t)blockIdx.y * gridDim.x + blockIdx.x, wave, lane);
+    if (gridDim.y > 1) mid_store_partial(acc, ws, (int64_t)blockIdx.y * gridDim.x + tile, wave, lane);
     else mid_store<MM::SCALED>(acc, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo, t0 + wt * 64, lane);
 }
 
@@ -233,8 +243,9 @@ __global__ __launch_bounds__(MD_THREADS) void k_dense_mid(const uint8_t* __restr
     const int row = lane & 31, q = lane >> 5;
     const int U_all = (int)(Kb / ROWB);
     const int u0 = (int)((int64_t)blockIdx.y * U_all / gridDim.y), U = (int)((int64_t)(blockIdx.y + 1) * U_all / gridDim.y) - u0;
-    const int64_t panel = blockIdx.x / tiles_t;
-    const int64_t t0 = (int64_t)(blockIdx.x - panel * tiles_t) * MD_TILE;
+    const int tile = mid_tile_of_block();
+    const int64_t panel = tile / tiles_t;
+    const int64_t t0 = (int64_t)(tile - panel * tiles_t) * MD_TILE;
 
     MidRowLoader la, lb;
     la.init(Wq + (int64_t)u0 * ROWB, Kb, panel * PANEL, O, wave, lane);
@@ -290,7 +301,7 @@ __global__ __launch_bounds__(MD_THREADS) void k_dense_mid(const uint8_t* __restr
         slot = slot == MD_D_RING - 1 ? 0 : slot + 1;
         lslot = lslot == MD_D_RING - 1 ? 0 : lslot + 1;
     }
-    if (gridDim.y > 1) mid_store_partial(acc, ws, (int64_t)blockIdx.y * gridDim.x + blockIdx.x, wave, lane);
+    if (gridDim.y > 1) mid_store_partial(acc, ws, (int64_t)blockIdx.y * gridDim.x + tile, wave, lane);
     else mid_store<MM::SCALED>(acc, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo, t0 + wt * 64, lane);
 }
 
