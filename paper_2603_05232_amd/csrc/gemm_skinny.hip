@@ -354,9 +354,10 @@ static ss_status launch_sparse_one(const void* XL, const float* s_x, const void*
     if (FPW == 1 && (int)grid < cu_count()) {
         hipLaunchKernelGGL((k_sparse_skinny<DT, TB, 1, 8>), dim3(grid, (unsigned)S), dim3(512), 0, stream, static_cast<const uint8_t*>(XL), s_x,
                            static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy, ws);
-        if (S > 1 && launch_status() == SS_OK)
-            hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
-                               static_cast<uint16_t*>(Y), ldy);
+        const ss_status first = launch_status();       // reading the status clears it: keep it
+        if (first != SS_OK || S <= 1) return first;
+        hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
+                           static_cast<uint16_t*>(Y), ldy);
     } else
         hipLaunchKernelGGL((k_sparse_skinny<DT, TB, FPW, 4>), dim3(grid), dim3(256), 0, stream, static_cast<const uint8_t*>(XL), s_x,
                            static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy, ws);
@@ -371,9 +372,10 @@ static ss_status launch_dense_one(const void* Xq, const float* s_x, const void* 
     if (FPW == 1 && (int)grid < cu_count()) {
         hipLaunchKernelGGL((k_dense_skinny<DT, TB, 1, 8>), dim3(grid, (unsigned)S), dim3(512), 0, stream, static_cast<const uint8_t*>(Xq), s_x,
                            static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, ws);
-        if (S > 1 && launch_status() == SS_OK)
-            hipLaunchKernelGGL((k_skinny_reduce<DT, TB, false>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
-                               static_cast<uint16_t*>(Y), ldy);
+        const ss_status first = launch_status();
+        if (first != SS_OK || S <= 1) return first;
+        hipLaunchKernelGGL((k_skinny_reduce<DT, TB, false>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
+                           static_cast<uint16_t*>(Y), ldy);
     } else
         hipLaunchKernelGGL((k_dense_skinny<DT, TB, FPW, 4>), dim3(grid), dim3(256), 0, stream, static_cast<const uint8_t*>(Xq), s_x,
                            static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, ws);

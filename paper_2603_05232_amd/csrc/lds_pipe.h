@@ -8,21 +8,34 @@ namespace ss {
 constexpr int ROWB = 128; // bytes of one LDS row of a row-major operand tile (one cache line)
 
 typedef __attribute__((address_space(3))) void lds_void;
-typedef __attribute__((address_space(1))) const void gbl_void;
 
-// 16 (or 4) bytes per lane, global -> LDS; the LDS address is wave-uniform base + lane * size.  The global
-// address is given as a wave-uniform pointer plus a 32-bit lane offset; the empty asm pins the uniform part
-// in scalar registers so that the load uses its scalar-base addressing form and the lane part stays one
-// 32-bit register (otherwise the compiler keeps a 64-bit per-lane address alive for every load stream).
-__device__ inline void lds_dma16(const uint8_t* uniform_base, uint32_t lane_off, void* lds_wave_base)
+// 16 (or 4) bytes per lane, global -> LDS; the LDS address is wave-uniform base + lane * size (the base
+// goes through M0).  The global address is a wave-uniform pointer in scalar registers plus a 32-bit lane
+// offset (the scalar-base form of the load: one address register per lane, no 64-bit address arithmetic).
+// The loads are written as assembly on purpose: the compiler's wait-count insertion treats a direct-to-LDS
+// load as an access to both address spaces and from then on turns every wait for an LDS read into a wait
+// for all of them; as opaque statements they leave its count of LDS reads exact (s_waitcnt lgkmcnt(n)
+// with n > 0 between the matrix instructions), and the kernels wait for the loads themselves with
+// explicit vmcnt counts anyway.
+__device__ inline uint32_t lds_address(const void* lds_ptr)
 {
-    asm volatile("" : "+s"(uniform_base));
-    __builtin_amdgcn_global_load_lds((gbl_void*)(uniform_base + lane_off), (lds_void*)lds_wave_base, 16, 0, 0);
+    return __builtin_amdgcn_readfirstlane((uint32_t)(uintptr_t)(const lds_void*)lds_ptr);
 }
-__device__ inline void lds_dma4(const uint8_t* uniform_base, uint32_t lane_off, void* lds_wave_base)
+__device__ inline void lds_dma16_at(const uint8_t* uniform_base, uint32_t lane_off, uint32_t lds_wave_addr)
 {
-    asm volatile("" : "+s"(uniform_base));
-    __builtin_amdgcn_global_load_lds((gbl_void*)(uniform_base + lane_off), (lds_void*)lds_wave_base, 4, 0, 0);
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_wave_addr), "v"(lane_off), "s"(uniform_base) : "memory", "m0");
+}
+__device__ inline void lds_dma4_at(const uint8_t* uniform_base, uint32_t lane_off, uint32_t lds_wave_addr)
+{
+    asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dword %1, %2" ::"s"(lds_wave_addr), "v"(lane_off), "s"(uniform_base) : "memory", "m0");
+}
+__device__ inline void lds_dma16(const uint8_t* uniform_base, uint32_t lane_off, const void* lds_wave_base)
+{
+    lds_dma16_at(uniform_base, lane_off, lds_address(lds_wave_base));
+}
+__device__ inline void lds_dma4(const uint8_t* uniform_base, uint32_t lane_off, const void* lds_wave_base)
+{
+    lds_dma4_at(uniform_base, lane_off, lds_address(lds_wave_base));
 }
 
 // Lane id read from the hardware.  Code that runs once per tile (loader set-up, epilogue) takes the lane id from

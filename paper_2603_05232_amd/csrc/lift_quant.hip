@@ -285,7 +285,8 @@ extern "C" ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_
     if (M < 0 || K <= 0 || ldx < K || K > (1 << 24) || M > 0x7FFFFFFF) return SS_ERR_SHAPE;
     if (in_dtype != SS_IN_F32 && in_dtype != SS_IN_BF16) return SS_ERR_DTYPE;
     if (!valid_dtype(out)) return SS_ERR_DTYPE;
-    if ((size_t)lift_lds_elems(K, N, elem_size(out)) * elem_size(out) > 64 * 1024) return SS_ERR_SHAPE;    // quantised row must fit in LDS
+    // the quantised row and the kernel's small reduction buffer (at most 64 bytes) must fit in 64 KiB of LDS
+    if ((size_t)lift_lds_elems(K, N, elem_size(out)) * elem_size(out) + 64 > 64 * 1024) return SS_ERR_SHAPE;
     if (M == 0) return SS_OK;
     if (!X || !X_lifted || (!unscaled(out) && !s_x)) return SS_ERR_NULL;
     if ((uintptr_t)X_lifted & 15) return SS_ERR_SHAPE;
