@@ -162,6 +162,22 @@ ss_status dense_gemm_ws(const void* Xq, const float* s_x, const void* Wq, const 
                         int64_t M, int64_t O, int64_t K, ss_dtype dtype, void* Y, int64_t ldy,
                         void* workspace, size_t workspace_bytes, void* stream);
 
+/* Fused lifting (Sec. 3.3 lifting operator realised inside the GEMM; the paper fuses it into quantisation, Alg. 1):
+ * the same linear layer for the 6:8 pattern (N = 4; any other N returns SS_ERR_BAD_PATTERN_N) computed from the
+ * UNLIFTED quantised activations Xq[M,K] (row stride ldx elements; what act_lift_quant writes with N = 2), so the
+ * lifted matrix is never materialised.  The weights are packed by slide_decompose_fused, which runs the same
+ * decomposition as slide_decompose (Alg. 2) but orders the windows for this kernel (opaque; sizes from
+ * slide_packed_sizes_fused); buffers of the two packers are not interchangeable.  Requires K * sizeof(element) % 128 == 0
+ * (pad X and W with zero columns otherwise), ldx * sizeof(element) % 16 == 0, 16-byte aligned pointers, O <= ldy < 2^22,
+ * M <= 2^24.  Same epilogue, accumulation rules and error behaviour as slide_sparse_gemm; INT8 results are identical
+ * to slide_sparse_gemm and dense_gemm, floating-point results differ in summation order only. */
+ss_status slide_packed_sizes_fused(int64_t O, int64_t K, int N, ss_dtype dtype, size_t* vals_bytes, size_t* meta_bytes);
+ss_status slide_decompose_fused(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype,
+                                void* w_vals, void* w_meta, int32_t* violations, void* stream);
+ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta,
+                                  const float* s_w, int64_t M, int64_t O, int64_t K, int64_t ldx, int N,
+                                  ss_dtype dtype, void* Y, int64_t ldy, void* stream);
+
 const char* ss_status_string(ss_status s);
 
 /* Library / packed-format version (bumped whenever the opaque layout changes). */

@@ -20,6 +20,7 @@ DTYPE_CODE = {"i8": SS_I8, "fp8": SS_FP8_E4M3, "bf16": SS_BF16, "fp16": SS_FP16}
 EXPORTS = ("slide_lifted_k", "slide_lifted_ld", "slide_packed_sizes", "slide_prune_quant", "slide_decompose",
            "slide_decompose_canonical", "act_lift_quant", "slide_sparse_gemm", "dense_gemm",
            "slide_gemm_workspace_bytes", "slide_sparse_gemm_ws", "dense_gemm_ws",
+           "slide_packed_sizes_fused", "slide_decompose_fused", "slide_sparse_gemm_fused",
            "ss_status_string", "slide_format_version")
 
 _lib = None
@@ -53,10 +54,14 @@ def load():
     lib.dense_gemm.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, i64, vp]
     lib.slide_sparse_gemm_ws.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, i64, vp, sz, vp]
     lib.dense_gemm_ws.argtypes = [vp, vp, vp, vp, i64, i64, i64, i32, vp, i64, vp, sz, vp]
+    lib.slide_packed_sizes_fused.argtypes = [i64, i64, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
+    lib.slide_decompose_fused.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
+    lib.slide_sparse_gemm_fused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, i32, vp, i64, vp]
     lib.slide_gemm_workspace_bytes.argtypes = [i64, i64, i64, i32]
     lib.slide_gemm_workspace_bytes.restype = sz
     for name in ("slide_packed_sizes", "slide_prune_quant", "slide_decompose", "slide_decompose_canonical",
-                 "act_lift_quant", "slide_sparse_gemm", "dense_gemm", "slide_sparse_gemm_ws", "dense_gemm_ws"):
+                 "act_lift_quant", "slide_sparse_gemm", "dense_gemm", "slide_sparse_gemm_ws", "dense_gemm_ws",
+                 "slide_packed_sizes_fused", "slide_decompose_fused", "slide_sparse_gemm_fused"):
         getattr(lib, name).restype = i32
     lib.ss_status_string.argtypes = [i32]
     lib.ss_status_string.restype = ctypes.c_char_p
@@ -198,4 +203,35 @@ def dense_gemm(Xq, s_x, Wq, s_w, dtype: str, out=None, workspace=None):
         _check(load().dense_gemm_ws(_ptr(Xq), _ptr(s_x), _ptr(Wq), _ptr(s_w), M, O, K, DTYPE_CODE[dtype], _ptr(out),
                                     out.stride(0), _ptr(workspace), workspace.numel() * workspace.element_size(), _stream()),
                "dense_gemm_ws")
+    return out
+
+
+def slide_packed_sizes_fused(O: int, K: int, N: int, dtype: str):
+    v, m = ctypes.c_size_t(), ctypes.c_size_t()
+    _check(load().slide_packed_sizes_fused(O, K, N, DTYPE_CODE[dtype], ctypes.byref(v), ctypes.byref(m)), "slide_packed_sizes_fused")
+    return int(v.value), int(m.value)
+
+
+def slide_decompose_fused(Wq: torch.Tensor, N: int, dtype: str, count_violations: bool = False):
+    """Wq[O,K] -> (w_vals, w_meta[, violations]) in the window order of slide_sparse_gemm_fused."""
+    O, K = Wq.shape
+    assert Wq.is_cuda and Wq.is_contiguous()
+    vb, mb = slide_packed_sizes_fused(O, K, N, dtype)
+    w_vals = torch.empty((vb,), dtype=torch.uint8, device=Wq.device)
+    w_meta = torch.empty((mb,), dtype=torch.uint8, device=Wq.device)
+    viol = torch.zeros((1,), dtype=torch.int32, device=Wq.device) if count_violations else None
+    _check(load().slide_decompose_fused(_ptr(Wq), O, K, N, DTYPE_CODE[dtype], _ptr(w_vals), _ptr(w_meta), _ptr(viol), _stream()),
+           "slide_decompose_fused")
+    return (w_vals, w_meta, viol) if count_violations else (w_vals, w_meta)
+
+
+def slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O: int, K: int, N: int, dtype: str, out=None):
+    """Y[M,O] bf16 = epilogue(Psi(Xq[M, :K]) . W'^T) from unlifted quantised activations (row stride = Xq.stride(0))."""
+    M = Xq.shape[0]
+    assert Xq.is_cuda and Xq.stride(1) == 1 and Xq.shape[1] >= K
+    if out is None:
+        out = torch.empty((M, O), dtype=torch.bfloat16, device=Xq.device)
+    ldx = Xq.stride(0) if M > 1 else Xq.shape[1]
+    _check(load().slide_sparse_gemm_fused(_ptr(Xq), _ptr(s_x), _ptr(w_vals), _ptr(w_meta), _ptr(s_w), M, O, K, ldx, N,
+                                          DTYPE_CODE[dtype], _ptr(out), out.stride(0), _stream()), "slide_sparse_gemm_fused")
     return out

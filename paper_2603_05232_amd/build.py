@@ -11,7 +11,7 @@ ROOT = os.path.dirname(PKG)
 CSRC = os.path.join(PKG, "csrc")
 OBJ = os.path.join(ROOT, "_build")
 LIB = os.path.join(PKG, "libslidesparse.so")
-SOURCES = ("lift_quant.hip", "decompose.hip", "gemm.hip", "gemm_skinny.hip", "gemm_mid.hip")
+SOURCES = ("lift_quant.hip", "decompose.hip", "gemm.hip", "gemm_skinny.hip", "gemm_mid.hip", "gemm_fused.hip")
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-ffp-contract=off",
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
          "-Wno-inline-asm",      # the direct-to-LDS loads name M0 as clobbered, which clang reports as a reserved register

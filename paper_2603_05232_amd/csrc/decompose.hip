@@ -133,8 +133,9 @@ template <int ES> struct SlideBlock {
     }
 };
 
-// packed form: one thread per (panel, 64-byte step, fragment, lane)
-template <int ES>
+// packed form: one thread per (panel, 64-byte step, fragment, lane).  FUSED: the window order of the GEMM that lifts
+// the activations itself (N = 4; fused_window in packed_layout.h) instead of the order of the lifted row.
+template <int ES, bool FUSED>
 __global__ __launch_bounds__(256) void k_decompose_packed(const typename Elem<ES>::T* __restrict__ Wq, int64_t O, int K, int N, bool fp,
                                                            uint4* __restrict__ vals, uint32_t* __restrict__ meta, int64_t nslots,
                                                            int nsteps, int32_t* __restrict__ violations)
@@ -160,9 +161,14 @@ __global__ __launch_bounds__(256) void k_decompose_packed(const typename Elem<ES
         const T* row = Wq + o * (int64_t)K;
 #pragma unroll
         for (int w = 0; w < NW; ++w) {
-            const int j = step * (2 * NW) + step_window<ES>(qa, w);
-            const int g = j / (N - 1), l = j - g * (N - 1);
-            if (g != g_held) {                           // a lane's windows ascend, so every block is loaded once
+            int g, l;
+            if constexpr (FUSED) fused_window<ES>(step, qa, w, g, l);
+            else {
+                const int j = step * (2 * NW) + step_window<ES>(qa, w);
+                g = j / (N - 1);
+                l = j - g * (N - 1);
+            }
+            if (g != g_held) {                           // windows of one block are neighbours in a lane, so every block is loaded once
                 B.load(row, K, N, g, fp);
                 g_held = g;
             }
@@ -203,6 +209,24 @@ extern "C" ss_status slide_packed_sizes(int64_t O, int64_t K, int N, ss_dtype dt
     return SS_OK;
 }
 
+template <bool FUSED>
+static ss_status launch_packed(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype, int64_t Kpb, void* w_vals, void* w_meta,
+                               int32_t* violations, void* stream)
+{
+    const int64_t npanels = (O + PANEL - 1) / PANEL;
+    const int nsteps = (int)(Kpb / FRAG_KB);
+    const int64_t nslots = npanels * nsteps * FRAGS_PER_PANEL * 64;
+    const dim3 grid((unsigned)((nslots + 255) / 256)), block(256);
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    if (elem_size(dtype) == 2)
+        hipLaunchKernelGGL((k_decompose_packed<2, FUSED>), grid, block, 0, s, static_cast<const uint16_t*>(Wq), O, (int)K, N, true,
+                           static_cast<uint4*>(w_vals), static_cast<uint32_t*>(w_meta), nslots, nsteps, violations);
+    else
+        hipLaunchKernelGGL((k_decompose_packed<1, FUSED>), grid, block, 0, s, static_cast<const uint8_t*>(Wq), O, (int)K, N, dtype == SS_FP8_E4M3,
+                           static_cast<uint4*>(w_vals), static_cast<uint32_t*>(w_meta), nslots, nsteps, violations);
+    return launch_status();
+}
+
 extern "C" ss_status slide_decompose(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype, void* w_vals, void* w_meta,
                                      int32_t* violations, void* stream)
 {
@@ -211,18 +235,34 @@ extern "C" ss_status slide_decompose(const void* Wq, int64_t O, int64_t K, int N
     const int64_t Kpb = lifted_ld(K, N, elem_size(dtype)) * elem_size(dtype);
     if (O == 0) return SS_OK;
     if (!Wq || !w_vals || !w_meta) return SS_ERR_NULL;
-    const int64_t npanels = (O + PANEL - 1) / PANEL;
-    const int nsteps = (int)(Kpb / FRAG_KB);
-    const int64_t nslots = npanels * nsteps * FRAGS_PER_PANEL * 64;
-    const dim3 grid((unsigned)((nslots + 255) / 256)), block(256);
-    hipStream_t s = static_cast<hipStream_t>(stream);
-    if (elem_size(dtype) == 2)
-        hipLaunchKernelGGL(k_decompose_packed<2>, grid, block, 0, s, static_cast<const uint16_t*>(Wq), O, (int)K, N, true,
-                           static_cast<uint4*>(w_vals), static_cast<uint32_t*>(w_meta), nslots, nsteps, violations);
-    else
-        hipLaunchKernelGGL(k_decompose_packed<1>, grid, block, 0, s, static_cast<const uint8_t*>(Wq), O, (int)K, N, dtype == SS_FP8_E4M3,
-                           static_cast<uint4*>(w_vals), static_cast<uint32_t*>(w_meta), nslots, nsteps, violations);
-    return launch_status();
+    return launch_packed<false>(Wq, O, K, N, dtype, Kpb, w_vals, w_meta, violations, stream);
+}
+
+// Fused order: lifted bytes per row = 192 per 128 unlifted bytes (whole super-units; columns at and beyond K are zero).
+static int64_t fused_lifted_row_bytes(int64_t K, ss_dtype dtype) { return (K * elem_size(dtype) + KSTEP - 1) / KSTEP * (3 * FRAG_KB); }
+
+extern "C" ss_status slide_packed_sizes_fused(int64_t O, int64_t K, int N, ss_dtype dtype, size_t* vals_bytes, size_t* meta_bytes)
+{
+    ss_status st = check_decompose(O, K, N, dtype);
+    if (st != SS_OK) return st;
+    if (N != 4) return SS_ERR_BAD_PATTERN_N;
+    if (!vals_bytes || !meta_bytes) return SS_ERR_NULL;
+    const int64_t Kpb = fused_lifted_row_bytes(K, dtype);
+    const int64_t Opad = (O + PANEL - 1) / PANEL * PANEL;
+    *vals_bytes = (size_t)(Opad * (Kpb / 2));
+    *meta_bytes = (size_t)(Opad * (Kpb / 8));
+    return SS_OK;
+}
+
+extern "C" ss_status slide_decompose_fused(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype, void* w_vals, void* w_meta,
+                                           int32_t* violations, void* stream)
+{
+    ss_status st = check_decompose(O, K, N, dtype);
+    if (st != SS_OK) return st;
+    if (N != 4) return SS_ERR_BAD_PATTERN_N;
+    if (O == 0) return SS_OK;
+    if (!Wq || !w_vals || !w_meta) return SS_ERR_NULL;
+    return launch_packed<true>(Wq, O, K, N, dtype, fused_lifted_row_bytes(K, dtype), w_vals, w_meta, violations, stream);
 }
 
 extern "C" ss_status slide_decompose_canonical(const void* Wq, int64_t O, int64_t K, int N, ss_dtype dtype, void* vals, uint8_t* idx,

@@ -42,6 +42,25 @@ template <int ES> __host__ __device__ inline int step_window(int qa, int w)
     return 2 * HW * (w / HW) + HW * qa + (w % HW);
 }
 
+// Fused order of the 6:8 pattern (N = 4), for the GEMM that takes unlifted activations and applies the lifting
+// operator on the way from LDS to the operand registers.  A super-unit is 128 unlifted bytes of a row = BL = 8 / ES
+// blocks per B-lane half = three steps.  B lane (n, qb) holds the 64 unlifted bytes [64 qb, 64 qb + 64) of the
+// super-unit as 16 registers; steps 3s and 3s+1 use registers 0..7 and 8..15 as they are (windows l = 0 and l = 2
+// of a block are its first and second half: no data movement), step 3s+2 uses the middle windows (l = 1) of all
+// the lane's blocks, built with one byte-align (8-bit types) or two register copies (16-bit types) per window.
+// So window slot wsl (0..BL-1) of B lane half qb in step 3s+J is
+//     J = 0, 1:  block (2s + qb) BL + J BL/2 + (wsl >> 1),  window l = 2 (wsl & 1)
+//     J = 2:     block (2s + qb) BL + wsl,                  window l = 1
+// and the A lane (qa, slot w) meets B lane half qb = w / HW, window slot wsl = HW qa + (w % HW) as in step_window.
+template <int ES> __host__ __device__ inline void fused_window(int step, int qa, int w, int& g, int& l)
+{
+    constexpr int HW = 4 / ES, BL = 8 / ES;
+    const int qb = w / HW, wsl = HW * qa + (w % HW);
+    const int s = step / 3, J = step - 3 * s;
+    l = J == 2 ? 1 : 2 * (wsl & 1);
+    g = (2 * s + qb) * BL + (J == 2 ? wsl : J * (BL / 2) + (wsl >> 1));
+}
+
 // slot of the 16-byte value group of (panel, step, fragment, lane); values are stored [panel][step][fragment][lane],
 // index words (4 bytes each, the upper half unused for bf16) [panel][step][lane][fragment], so that one 16-byte
 // read hands a lane the words of all four fragments

@@ -1,0 +1,100 @@
+"""GPU parity of the fused-lifting path (slide_decompose_fused + slide_sparse_gemm_fused, 6:8 only): the GEMM takes the
+unlifted quantised activations and must give the oracle's linear layer, bit-exact for INT8."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import slide_oracle as so
+from oracle import gemm_ref
+from paper_2603_05232_amd import binding, synth
+from test_gpu_parity import dev, host, bits16, to_dev_q, from_dev_q, _float_gemm_check
+
+pytestmark = pytest.mark.gpu
+DEV = "cuda:0"
+N = 4
+
+
+@pytest.mark.parametrize("M,O,K", [(16, 512, 512),         # the anchor case
+                                   (300, 640, 1024),       # ragged tokens and channels
+                                   (1, 384, 128),          # one token, one super-unit
+                                   (257, 130, 256),        # two super-units, one ragged panel
+                                   (64, 256, 384),         # three super-units (no steady iteration)
+                                   (40, 128, 512),         # four: one steady iteration
+                                   (513, 300, 896)])       # seven, three token tiles
+def test_fused_gemm_int8(M, O, K):
+    X = synth.activations(M, K, seed=M + O)
+    W = synth.weights(O, K, seed=M + O)
+    ref = so.linear_reference(X, W, N, "i8")
+    Wq, s_w = binding.slide_prune_quant(dev(W), N, "i8")
+    w_vals, w_meta, viol = binding.slide_decompose_fused(Wq, N, "i8", count_violations=True)
+    Xq, s_x = binding.act_lift_quant(dev(X), 2, "i8")          # plain per-token quantisation: K bytes per token
+    assert np.array_equal(host(Xq)[:, :K], ref["Xq"])
+    Y = binding.slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O, K, N, "i8")
+    assert int(host(viol)[0]) == 0
+    assert np.array_equal(bits16(Y), ref["Y"])
+
+
+def test_fused_gemm_two_rounds_full_output_and_strides():
+    """More tiles than compute units (17 x 18 = 306 tiles of 256 x 256: two persistent rounds), ragged edges, random
+    sparse supports (windows with 0, 1 and 2 stored values), strided X and Y; every output element against the C oracle."""
+    rng = np.random.default_rng(5)
+    M, O, K = 4300, 4400, 256
+    Wq = rng.integers(-127, 128, size=(O, K)).astype(np.int8)
+    keep = np.argsort(rng.random((O, K // 8, 8)), axis=-1) < rng.integers(0, 7, size=(O, K // 8, 1))
+    Wq = (Wq.reshape(O, K // 8, 8) * keep).reshape(O, K).astype(np.int8)
+    Xq = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    s_x = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    s_w = rng.uniform(1e-4, 1e-3, O).astype(np.float32)
+    exp = so.epilogue(gemm_ref.gemm_i8_i64(Xq, Wq), s_x, s_w, "i8")
+    w_vals, w_meta = binding.slide_decompose_fused(dev(Wq), N, "i8")
+    xbuf = torch.zeros((M, K + 128), dtype=torch.int8, device=DEV)
+    xbuf[:, :K] = dev(Xq)
+    ybuf = torch.full((M, O + 64), -1.0, dtype=torch.bfloat16, device=DEV)
+    binding.slide_sparse_gemm_fused(xbuf, dev(s_x), w_vals, w_meta, dev(s_w), O, K, N, "i8", out=ybuf[:, :O])
+    assert np.array_equal(bits16(ybuf[:, :O].contiguous()), exp)
+    assert torch.all(ybuf[:, O:] == -1.0)
+
+
+@pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
+@pytest.mark.parametrize("M,O,K", [(16, 512, 512), (300, 640, 1024), (257, 130, 256)])
+def test_fused_gemm_float(dtype, M, O, K):
+    X = synth.activations(M, K, seed=M + O)
+    W = synth.weights(O, K, seed=M + O)
+    if M > 2:
+        X[1] = 0.0
+    ref = so.linear_reference(X, W, N, dtype)
+    Wq, s_w = binding.slide_prune_quant(dev(W), N, dtype)
+    w_vals, w_meta = binding.slide_decompose_fused(Wq, N, dtype)
+    Xq, s_x = binding.act_lift_quant(dev(X), 2, dtype)
+    Y = binding.slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O, K, N, dtype)
+    _float_gemm_check(bits16(Y), ref, dtype)
+    # small integers: every product and partial sum is exact, so the result must be the rounded exact one
+    rng = np.random.default_rng(K + M)
+    Xi = rng.integers(-4, 5, size=(M, K)).astype(np.float32)
+    Wi = so.prune_2n(rng.integers(-4, 5, size=(O, K)).astype(np.float32), N)
+    if dtype == "fp8":
+        Xq_i, Wq_i = so.fp8_e4m3_encode(Xi), so.fp8_e4m3_encode(Wi)
+        sx = np.ones(M, np.float32); sw = np.ones(O, np.float32)
+    else:
+        to_bits = so.bf16_bits if dtype == "bf16" else so.fp16_bits
+        Xq_i, Wq_i = to_bits(Xi), to_bits(Wi)
+        sx = sw = None
+    exp = so.epilogue(so.gemm_exact(Xq_i, Wq_i, dtype), sx, sw, dtype)
+    w_vals, w_meta = binding.slide_decompose_fused(to_dev_q(Wq_i, dtype), N, dtype)
+    sxd = None if sx is None else dev(sx)
+    swd = None if sw is None else dev(sw)
+    Ys = binding.slide_sparse_gemm_fused(to_dev_q(Xq_i, dtype), sxd, w_vals, w_meta, swd, O, K, N, dtype)
+    assert np.array_equal(bits16(Ys), exp)
+
+
+def test_fused_rejects_other_patterns_and_ragged_k():
+    Wq = torch.zeros((128, 256), dtype=torch.int8, device=DEV)
+    with pytest.raises(binding.SlideSparseError) as e:
+        binding.slide_decompose_fused(Wq, 3, "i8")
+    assert e.value.code == 2
+    w_vals, w_meta = binding.slide_decompose_fused(Wq, 4, "i8")
+    Xq = torch.zeros((4, 256), dtype=torch.int8, device=DEV)
+    s = torch.ones((128,), dtype=torch.float32, device=DEV)
+    with pytest.raises(binding.SlideSparseError) as e:
+        binding.slide_sparse_gemm_fused(Xq, s[:4], w_vals, w_meta, s, 128, 200, 4, "i8")     # K * es not a multiple of 128
+    assert e.value.code == 3
