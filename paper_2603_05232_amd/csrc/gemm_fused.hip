@@ -73,8 +73,9 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
     typedef Mma<DT> MM;
     constexpr int W = 2 * WT, NBF = 8 / WT, NM = 4 * NBF, ES = MM::ES;
     constexpr int LB = 32 / W;                       // token-tile loads per wavefront and super-unit (1 KB each)
-    constexpr int APS = 8 / W;                       // weight pieces per wavefront and step: APS x 1 KB of values, APS x 256 B of index words
-    constexpr int LG = 3 * 2 * APS;                  // weight loads per wavefront and super-unit
+    constexpr int APS = 8 / W;                       // 1 KB pieces of stored values per wavefront and step
+    constexpr int IPW = (6 + W - 1) / W;             // 1 KB pieces of index words per wavefront and super-unit (6 per tile: 2 panels x 3 steps; spare turns repeat a piece)
+    constexpr int LG = 3 * APS + IPW;                // weight loads per wavefront and super-unit
     constexpr int L = LG + LB;
     constexpr int PRE_B = W == 4 ? 2 : 1;            // token tiles of the next tile requested before the epilogue (staging takes the other ring slots)
     static_assert(L <= (3 * NM) / 2, "one direct load behind every second matrix instruction");
@@ -86,9 +87,12 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
     const int nsteps = 3 * U;
     const int64_t npanels = (O + PANEL - 1) / PANEL;
     const int pw = (wave * APS) >> 2, f0 = (wave * APS) & 3;            // this wavefront's weight pieces: panel pw of the tile, fragments f0 .. f0 + APS - 1
-    const uint32_t a_wave = lds0 + pw * 4096 + f0 * 1024, i_wave = lds0 + F_AIDX + pw * 1024 + f0 * 256;
+    const uint32_t a_wave = lds0 + pw * 4096 + f0 * 1024;
+    int ip[IPW], ij[IPW];                           // this wavefront's index-word pieces in the steady state: panel, step within the super-unit
+#pragma unroll
+    for (int e = 0; e < IPW; ++e) { const int q = (wave + e * W) % 6; ip[e] = q / 3; ij[e] = q % 3; }
     const uint32_t b_wave = lds0 + F_B_OFF + wave * 1024;
-    const uint32_t lane16 = lane * 16, lane4 = lane * 4;
+    const uint32_t lane16 = lane * 16;
 
     // LDS byte offsets of this lane's operand reads (ring slot and fragment / chunk are added as they come)
     const uint32_t va = wo * 4096 + lane * 16, vi = F_AIDX + wo * 1024 + lane * 16;
@@ -101,7 +105,7 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
     }
 
     // Per-tile state of the loaders, set up for the next tile before the current tile's epilogue.
-    const uint8_t *b_src = nullptr, *av_src = nullptr, *am_src = nullptr;
+    const uint8_t *b_src = nullptr, *av_src = nullptr, *am_tile[2] = {nullptr, nullptr};
     uint32_t boff[LB];
     int64_t o_blk = 0, t_blk = 0;
     auto setup_tile = [&](int to, int tt) {
@@ -119,16 +123,20 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
         int64_t panel = (int64_t)to * 2 + pw;
         panel = panel < npanels ? panel : npanels - 1;
         av_src = w_vals + (panel * nsteps * 4 + f0) * 1024;
-        am_src = w_meta + panel * nsteps * 1024 + f0 * 256;
+#pragma unroll
+        for (int pp = 0; pp < 2; ++pp) {
+            int64_t pn = (int64_t)to * 2 + pp;
+            pn = pn < npanels ? pn : npanels - 1;
+            am_tile[pp] = w_meta + pn * nsteps * 1024;
+        }
     };
-    // the 2 APS weight loads of step k into ring slot `aslot`, the LB token loads of super-unit u into ring slot `bslot`
+    // the weight loads of step k into ring slot `aslot` (the index words of the two panels by wavefronts 0 and 1), the
+    // LB token loads of super-unit u into ring slot `bslot`
     auto load_a_step = [&](int k, int aslot) {
         const uint8_t* av = av_src + (int64_t)k * 4096;
-        const uint8_t* am = am_src + (int64_t)k * 1024;
 #pragma unroll
         for (int e = 0; e < APS; ++e) lds_dma16_at(av + e * 1024, lane16, a_wave + aslot * F_ASTEP + e * 1024);
-#pragma unroll
-        for (int e = 0; e < APS; ++e) lds_dma4_at(am + e * 256, lane4, i_wave + aslot * F_ASTEP + e * 256);
+        if (wave < 2) lds_dma16_at((wave ? am_tile[1] : am_tile[0]) + (int64_t)k * 1024, lane16, lds0 + aslot * F_ASTEP + F_AIDX + wave * 1024);
     };
     auto load_b_unit = [&](int u, int bslot) {
 #pragma unroll
@@ -206,8 +214,14 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
             // scalar parts of the direct loads of this iteration: steps k_ld .. k_ld + 2 go to ring slots par + 4, par + 5, par (mod 6)
             const int k_ld = 3 * u + 4;
             const uint8_t* av = av_src + (int64_t)k_ld * 4096;
-            const uint8_t* am = am_src + (int64_t)k_ld * 1024;
             const uint32_t s4 = (par == 0 ? 4 : 1) * F_ASTEP, s5 = (par == 0 ? 5 : 2) * F_ASTEP, s6 = (par == 0 ? 0 : 3) * F_ASTEP;
+            const uint8_t* am[IPW];
+            uint32_t im[IPW];                         // this wavefront's index-word pieces: source, LDS destination
+#pragma unroll
+            for (int e = 0; e < IPW; ++e) {
+                am[e] = (ip[e] ? am_tile[1] : am_tile[0]) + (int64_t)(k_ld + ij[e]) * 1024;
+                im[e] = lds0 + F_AIDX + ip[e] * 1024 + (ij[e] == 0 ? s4 : ij[e] == 1 ? s5 : s6);
+            }
             const uint8_t* bsrc = b_src + (int64_t)(u + 3) * 128;
             const uint32_t b_ld = b_wave + (bn == 0 ? 2 : bn - 1) * F_BSLOT;
             if constexpr (MODE == IT_TAIL) {
@@ -226,12 +240,13 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
                     const int d = gi >> 1;
                     if ((gi & 1) && d < L) {
 #endif
-                        if (d < LG) {
-                            const int jj = d / (2 * APS), x = d % (2 * APS);
+                        if (d < 3 * APS) {
+                            const int jj = d / APS, x = d % APS;
                             const uint32_t so = jj == 0 ? s4 : jj == 1 ? s5 : s6;
-                            if (x < APS) lds_dma16_at(av + jj * 4096 + x * 1024, lane16, a_wave + so + x * 1024);
-                            else lds_dma4_at(am + jj * 1024 + (x - APS) * 256, lane4, i_wave + so + (x - APS) * 256);
-                        } else {
+                            if (!(SS_EXP_SKIP & 128)) lds_dma16_at(av + jj * 4096 + x * 1024, lane16, a_wave + so + x * 1024);
+                        } else if (d < LG) {
+                            if (!(SS_EXP_SKIP & 32)) lds_dma16_at(am[d - 3 * APS], lane16, im[d - 3 * APS]);
+                        } else if (!(SS_EXP_SKIP & 64)) {
                             const int i = d - LG;
                             lds_dma16_at(bsrc, boff[i < LB ? i : 0], b_ld + i * W * 1024);
                         }
@@ -317,6 +332,7 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
 #if SS_EXP_NOWAIT
             wait_lgkm0();
 #else
+            if (SS_EXP_SKIP & (32 | 64 | 128)) wait_vmcnt<0>(); else
             wait_vmcnt<LB>();                          // everything but the token tile just requested has landed; own reads have returned
 #endif
             if (!(SS_EXP_SKIP & 8)) wg_barrier();
