@@ -2,10 +2,12 @@
 """Benchmark of the SlideSparse hot path on one MI355X.
 
 One step = the per-request path of the four Qwen2.5-7B-shaped linear layers at 6:8 INT8,
-M = 8192 tokens: act_lift_quant followed by slide_sparse_gemm for qkv, o, gate_up and down
-(weights are pruned, quantised and decomposed once, before timing, as the paper does
-offline).  The same step with plain quantisation + dense_gemm at the original K is timed
-beside it as the speed-up denominator.  Prints one JSON line.
+M = 8192 tokens, for qkv, o, gate_up and down (weights are pruned, quantised and decomposed
+once, before timing, as the paper does offline).  The headline step is per-token
+quantisation (act_lift_quant with N = 2) followed by slide_sparse_gemm_fused, which applies
+the lifting operator inside the GEMM; the step with the lifted matrix materialised
+(act_lift_quant with N = 4 + slide_sparse_gemm) is timed beside it, and so is plain
+quantisation + dense_gemm at the original K, the speed-up denominator.  Prints one JSON line.
 """
 from __future__ import annotations
 
@@ -23,12 +25,11 @@ sys.path.insert(0, ROOT)
 PEAK_INT8_DENSE_TOPS = 5033.0      # MI355X published dense INT8; v_smfmac runs at the same MAC rate with 2x the K
 PEAK_INT8_SPARSE_TOPS = 2 * PEAK_INT8_DENSE_TOPS
 PEAK_HBM_GBS = 8000.0
-# HBM traffic of the sparse GEMM kernel per launch (mean over the four layer launches of a step), from the
-# FETCH_SIZE and WRITE_SIZE counters of two rocprofv3 --pmc runs of this script, each scaled by what the same
-# counter reads for the 256 MiB elementwise copy of --copy-calibration (FETCH_SIZE x 1.9999, WRITE_SIZE x 1.0);
-# summary and commands in profiles/gemm_qwen7b_m8192_int8_hbm_traffic.txt.  Bytes per launch:
-# 1.082e9 fetched (L2 misses, including those the memory-side cache serves) + 2.035e8 written.
-SPARSE_GEMM_TRAFFIC = 1.2853e9
+# Fabric-side traffic of the sparse GEMM kernels per launch (mean over the four layer launches of a step): a RECORDED
+# constant, not measured by the run that prints it.  It comes from the FETCH_SIZE and WRITE_SIZE counters of two
+# rocprofv3 --pmc runs of this script, each scaled by what the same counter reads for the 256 MiB elementwise copy of
+# --copy-calibration; summary and commands in profiles/gemm_qwen7b_m8192_int8_hbm_traffic.txt.
+RECORDED_TRAFFIC = {"fused": None, "lifted": 1.2853e9}
 N_PATTERN = 4                      # 6:8
 M_TOKENS = 8192
 
@@ -188,6 +189,7 @@ def main():
         W = torch.from_numpy(synth.weights(O, K, seed=li)).to(dev)
         Wq, s_w = binding.slide_prune_quant(W, N, "i8")
         w_vals, w_meta, viol = binding.slide_decompose(Wq, N, "i8", count_violations=True)
+        fw_vals, fw_meta = binding.slide_decompose_fused(Wq, N, "i8")
         # the offline weight path once more under HIP events (reported, not part of the step)
         ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
         ev[0].record()
@@ -199,7 +201,8 @@ def main():
         offline.append((name, O * K, ev[0].elapsed_time(ev[1]), ev[1].elapsed_time(ev[2])))
         del W
         Kp = binding.slide_lifted_k(K, N)
-        st = dict(name=name, K=K, O=O, Kp=Kp, X=X, Wq=Wq, s_w=s_w, w_vals=w_vals, w_meta=w_meta,
+        st = dict(name=name, K=K, O=O, Kp=Kp, X=X, Wq=Wq, s_w=s_w, w_vals=w_vals, w_meta=w_meta, fw_vals=fw_vals, fw_meta=fw_meta,
+                  Yf=torch.empty((M, O), dtype=torch.bfloat16, device=dev),
                   XL=torch.empty((M, Kp), dtype=torch.int8, device=dev), Xq=torch.empty((M, K), dtype=torch.int8, device=dev),
                   s_x=torch.empty((M,), dtype=torch.float32, device=dev), s_xd=torch.empty((M,), dtype=torch.float32, device=dev),
                   Y=torch.empty((M, O), dtype=torch.bfloat16, device=dev), Yd=torch.empty((M, O), dtype=torch.bfloat16, device=dev))
@@ -212,6 +215,14 @@ def main():
             del W, Wq24
         state.append(st)
     torch.cuda.synchronize()
+
+    def fused_step(ev=None):
+        for i, s in enumerate(state):
+            if ev: ev[i][0].record()
+            binding.act_lift_quant(s["X"], 2, "i8", out=s["Xq"], s_x=s["s_xd"])
+            if ev: ev[i][1].record()
+            binding.slide_sparse_gemm_fused(s["Xq"], s["s_xd"], s["fw_vals"], s["fw_meta"], s["s_w"], s["O"], s["K"], N, "i8", out=s["Yf"])
+            if ev: ev[i][2].record()
 
     def sparse_step(ev=None):
         for i, s in enumerate(state):
@@ -268,14 +279,17 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    t_sparse = timed(sparse_step)
+    t_fused = timed(fused_step)
+    t_lifted = timed(sparse_step)
     t_dense = timed(dense_step)
     reps = max(5, min(args.steps, 50))
-    k_sparse = per_kernel(sparse_step, reps)
+    k_fused = per_kernel(fused_step, reps)
+    k_lifted = per_kernel(sparse_step, reps)
     k_dense = per_kernel(dense_step, reps)
+    t_sparse, k_sparse = t_fused, k_fused             # the headline path
 
-    # parity spot check inside the bench: sparse and dense paths must agree bit for bit
-    same = all(bool(torch.equal(s["Y"], s["Yd"])) for s in state)
+    # parity spot check inside the bench: both sparse paths and the dense path must agree bit for bit
+    same = all(bool(torch.equal(s["Yf"], s["Yd"])) and bool(torch.equal(s["Y"], s["Yd"])) for s in state)
     g24_ms = None
     if args.native_2_4:
         k_24 = per_kernel(native24_step, reps)       # (overwrites Yd; after the comparison)
@@ -285,14 +299,18 @@ def main():
     useful_ops = sum(2.0 * M * s["O"] * s["K"] for s in state)
     gemm_ms = float(k_sparse[:, 1].sum())
     dgemm_ms = float(k_dense[:, 1].sum())
-    lift_ms = float(k_sparse[:, 0].sum())
+    lift_ms = float(k_lifted[:, 0].sum())
+    lifted_gemm_ms = float(k_lifted[:, 1].sum())
     quant_ms = float(k_dense[:, 0].sum())
     executed_tops = (hw_ops / 2) / (gemm_ms * 1e-3) * 1e-12          # MACs actually issued x 2
     in_bytes = 4 if args.act_dtype == "fp32" else 2
     lift_bytes = sum(M * (s["K"] * in_bytes + s["Kp"] + 4) for s in state)
+    quant_bytes = sum(M * (s["K"] * in_bytes + s["K"] + 4) for s in state)
+    fq_ms = float(k_sparse[:, 0].sum())
     per_layer = {s["name"]: {"K": s["K"], "O": s["O"], "K_lifted": s["Kp"],
-                             "lift_ms": float(k_sparse[i, 0]), "sparse_gemm_ms": float(k_sparse[i, 1]),
-                             "quant_ms": float(k_dense[i, 0]), "dense_gemm_ms": float(k_dense[i, 1]),
+                             "quant_ms": float(k_sparse[i, 0]), "sparse_gemm_ms": float(k_sparse[i, 1]),
+                             "lift_ms": float(k_lifted[i, 0]), "lifted_sparse_gemm_ms": float(k_lifted[i, 1]),
+                             "dense_quant_ms": float(k_dense[i, 0]), "dense_gemm_ms": float(k_dense[i, 1]),
                              "sparse_hw_tops": 2.0 * M * s["O"] * s["Kp"] / (k_sparse[i, 1] * 1e-3) * 1e-12,
                              "dense_tops": 2.0 * M * s["O"] * s["K"] / (k_dense[i, 1] * 1e-3) * 1e-12,
                              "gemm_speedup": float(k_dense[i, 1] / k_sparse[i, 1])}
@@ -302,18 +320,25 @@ def main():
         "value": hw_ops / t_sparse * 1e-12, "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_sparse * 1e3,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
-        "config": {"workload": f"Qwen2.5-7B linears (qkv,o,gate_up,down), 6:8 INT8, M={M} tokens: act_lift_quant + slide_sparse_gemm per layer",
+        "config": {"workload": f"Qwen2.5-7B linears (qkv,o,gate_up,down), 6:8 INT8, M={M} tokens: per-token quantisation + slide_sparse_gemm_fused "
+                               "(lifting applied inside the GEMM) per layer",
                    "pattern": "6:8", "tokens": M, "activations": args.act_dtype},
-        "value_definition": "sum over layers of 2*M*O*K_lifted (hardware-counted ops) / time of the whole step (lifting included)",
+        "value_definition": "sum over layers of 2*M*O*K_lifted (hardware-counted ops; 1.5x the useful 2*M*O*K) / time of the whole step "
+                            "(quantisation included; lifting happens inside the GEMM)",
         "gemm_only_hw_tops": hw_ops / (gemm_ms * 1e-3) * 1e-12,
         "gemm_only_useful_tops": useful_ops / (gemm_ms * 1e-3) * 1e-12,
         "dense_gemm_tops": useful_ops / (dgemm_ms * 1e-3) * 1e-12,
         "speedup_gemm_vs_own_dense": dgemm_ms / gemm_ms,
         "speedup_layer_vs_own_dense": t_dense / t_sparse,
         "speedup_bound_N_over_N_minus_1": N / (N - 1.0),
-        "lift_overhead_vs_quant_only": lift_ms / quant_ms,
+        "lifted_path": {"note": "the same layers with the lifted matrix materialised: act_lift_quant (N = 4) + slide_sparse_gemm",
+                        "ms_per_step": t_lifted * 1e3, "lift_ms": lift_ms, "gemm_ms": lifted_gemm_ms,
+                        "gemm_only_hw_tops": hw_ops / (lifted_gemm_ms * 1e-3) * 1e-12,
+                        "frac_of_sparse_peak": hw_ops / (lifted_gemm_ms * 1e-3) * 1e-12 / PEAK_INT8_SPARSE_TOPS,
+                        "speedup_gemm_vs_own_dense": dgemm_ms / lifted_gemm_ms, "speedup_layer_vs_own_dense": t_dense / t_lifted,
+                        "lift_overhead_vs_quant_only": lift_ms / quant_ms, "recorded_traffic_bytes": RECORDED_TRAFFIC["lifted"]},
         "paper_context": "1.33x end-to-end at 6:8 INT8 on A100, Qwen2.5-7B prefill M=8192 (other hardware, not a target)",
-        "dense_ms_per_step": t_dense * 1e3, "lift_ms": lift_ms, "quant_only_ms": quant_ms,
+        "dense_ms_per_step": t_dense * 1e3, "quant_ms": float(k_sparse[:, 0].sum()), "dense_quant_ms": quant_ms,
         "sparse_equals_dense_bitwise": same,
         "per_layer": per_layer,
         "offline_weight_path": {"note": "slide_prune_quant (fp32 weights in) and slide_decompose (Alg. 2 + 2:4 compression + packing), one "
@@ -322,16 +347,21 @@ def main():
                                 "decompose_ms": {n: d for n, _, _, d in offline},
                                 "decompose_GBps_of_weight_bytes": sum(b for _, b, _, _ in offline) / sum(d for _, _, _, d in offline) * 1e-6,
                                 "prune_quant_GBps_of_weight_bytes": sum(b for _, b, _, _ in offline) / sum(p for _, _, p, _ in offline) * 1e-6},
-        "roofline": {"bound": "mfma", "achieved": executed_tops, "peak": PEAK_INT8_DENSE_TOPS, "unit": "TFLOP/s",
-                     "frac": executed_tops / PEAK_INT8_DENSE_TOPS, "traffic": SPARSE_GEMM_TRAFFIC,
-                     "kernel": "ss::k_sparse<0> (slide_sparse_gemm, INT8), mean over the four layer launches of a step",
+        "roofline": {"bound": "mfma", "achieved": executed_tops, "peak": PEAK_INT8_DENSE_TOPS, "unit": "TOP/s",
+                     "frac": executed_tops / PEAK_INT8_DENSE_TOPS, "traffic": RECORDED_TRAFFIC["fused"],
+                     "kernel": "ss::k_sparse_fused<0, 4> (slide_sparse_gemm_fused, INT8), mean over the four layer launches of a step",
                      "note": "INT8 ops; achieved = executed MACs x 2 = M*O*K_lifted per launch / HIP-event duration; "
-                             "identical to hardware-counted 2*M*O*K_lifted against the 2x sparse peak"},
+                             "identical to hardware-counted 2*M*O*K_lifted against the 2x sparse peak; traffic is a recorded "
+                             "constant from an earlier rocprofv3 --pmc run of this script (null until recorded)"},
         "roofline_dense": {"bound": "mfma", "achieved": useful_ops / (dgemm_ms * 1e-3) * 1e-12, "peak": PEAK_INT8_DENSE_TOPS,
-                           "unit": "TFLOP/s", "frac": useful_ops / (dgemm_ms * 1e-3) * 1e-12 / PEAK_INT8_DENSE_TOPS,
+                           "unit": "TOP/s", "frac": useful_ops / (dgemm_ms * 1e-3) * 1e-12 / PEAK_INT8_DENSE_TOPS,
                            "kernel": "ss::k_dense<0> (dense_gemm, INT8)"},
+        "roofline_quant": {"bound": "hbm", "achieved": quant_bytes / (fq_ms * 1e-3) * 1e-9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
+                           "frac": quant_bytes / (fq_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS,
+                           "kernel": f"k_act_lift_quant, N = 2: per-token quantisation ({args.act_dtype} in, int8 out), the headline step's first kernel"},
         "roofline_lift": {"bound": "hbm", "achieved": lift_bytes / (lift_ms * 1e-3) * 1e-9, "peak": PEAK_HBM_GBS, "unit": "GB/s",
-                          "frac": lift_bytes / (lift_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS, "kernel": f"k_act_lift_quant ({args.act_dtype} in, int8 out)"},
+                          "frac": lift_bytes / (lift_ms * 1e-3) * 1e-9 / PEAK_HBM_GBS,
+                          "kernel": f"k_act_lift_quant, N = 4: fused quantise + lift of the lifted path ({args.act_dtype} in, int8 out)"},
     }
     if args.vendor_baseline:
         vend = {}
@@ -353,7 +383,9 @@ def main():
         # Sec. 5 efficiency: measured speed-up over what native 2:4 on the same kernels predicts, S_2:4 / gamma
         out["native_2_4_gemm_ms"] = g24_ms
         out["speedup_native_2_4_vs_own_dense"] = dgemm_ms / g24_ms
-        out["efficiency_vs_native_2_4"] = (dgemm_ms / gemm_ms) / ((dgemm_ms / g24_ms) / (2.0 - 2.0 / N))
+        # (native 2:4 runs on the kernel of the lifted path, so that path is the like-for-like numerator)
+        out["efficiency_vs_native_2_4"] = (dgemm_ms / lifted_gemm_ms) / ((dgemm_ms / g24_ms) / (2.0 - 2.0 / N))
+        out["efficiency_fused_vs_native_2_4"] = (dgemm_ms / gemm_ms) / ((dgemm_ms / g24_ms) / (2.0 - 2.0 / N))
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(layers, args.cpu_sample_tokens, args.cpu_sample_channels)
     print(json.dumps(out))

@@ -227,20 +227,21 @@ __global__ __launch_bounds__(G_THREADS) void k_dense(const uint8_t* __restrict__
             t += NSUB;
         }
         wait_lgkm0();
+        // this sub-tile of Y and its token scales (requested here: they arrive behind the last matrix instructions)
+        const int64_t o_sub = o_blk + wo * 128, t_sub = t_blk + wt * (32 * NBF);
+        const int64_t rows = M - t_sub, cols = O - o_sub;          // <= 0: nothing of this sub-tile exists
+        const bool any = rows > 0 && cols > 0;
+        const int rows_left = any ? (int)(rows > 64 ? 64 : rows) : 0, cols_left = any ? (int)(cols > 128 ? 128 : cols) : 0;
+        float sx[NBF];
+        load_token_scales<MM::SCALED>(sx, MM::SCALED && any ? s_x + t_sub : s_x, rows_left);
         sub_step(t + NSUB - 1, odd, std::false_type{}, no_loads, 0);
         wg_barrier();                                 // every wave is done with the operand tiles: LDS becomes staging
-        const int64_t o_cur = o_blk, t_cur = t_blk;
+        uint16_t* const Y_sub = any ? Y + t_sub * ldy + o_sub : Y;
+        settle(sx);                                   // the token scales have arrived: no wait for them behind the loads requested next
         have = tile_of_round(round + 1, tiles_o, tiles_t, to, tt);
         if (have) { setup_tile(to, tt); issue(0); issue_scales((round + 1) & 1); }
-        {
-            const int64_t o_sub = o_cur + wo * 128, t_sub = t_cur + wt * (32 * NBF);
-            const int64_t rows = M - t_sub, cols = O - o_sub;      // <= 0: nothing of this sub-tile exists
-            const bool any = rows > 0 && cols > 0;
-            store_tile<MM::SCALED>(acc, MM::SCALED && any ? s_x + t_sub : s_x,
-                                   reinterpret_cast<const float*>(smem + D_SW_OFF + (round & 1) * SW_BYTES) + wo * 128,
-                                   any ? Y + t_sub * ldy + o_sub : Y, (uint32_t)ldy,
-                                   any ? (int)(rows > 64 ? 64 : rows) : 0, any ? (int)(cols > 128 ? 128 : cols) : 0, stage);
-        }
+        store_tile<MM::SCALED, 32, false>(acc, sx, reinterpret_cast<const float*>(smem + D_SW_OFF + (round & 1) * SW_BYTES) + wo * 128, Y_sub,
+                                   (uint32_t)ldy, rows_left, cols_left, stage);
     }
 }
 
@@ -405,20 +406,21 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse(const uint8_t* __restrict_
             slot = nslot;
         }
         wait_lgkm0();
+        // this sub-tile of Y and its token scales (requested here: they arrive behind the last matrix instructions)
+        const int64_t o_sub = o_blk + wo * 128, t_sub = t_blk + wt * (32 * NBF);
+        const int64_t rows = M - t_sub, cols = O - o_sub;          // <= 0: nothing of this sub-tile exists
+        const bool any = rows > 0 && cols > 0;
+        const int rows_left = any ? (int)(rows > 64 ? 64 : rows) : 0, cols_left = any ? (int)(cols > 128 ? 128 : cols) : 0;
+        float sx[NBF];
+        load_token_scales<MM::SCALED>(sx, MM::SCALED && any ? s_x + t_sub : s_x, rows_left);
         sub_step(slot, 0, std::false_type{}, no_loads, 0, 0);
         wg_barrier();                                 // every wave is done with the operand tiles: LDS becomes staging
-        const int64_t o_cur = o_blk, t_cur = t_blk;
+        uint16_t* const Y_sub = any ? Y + t_sub * ldy + o_sub : Y;
+        settle(sx);                                   // the token scales have arrived: no wait for them behind the loads requested next
         have = tile_of_round(round + 1, tiles_o, tiles_t, to, tt);
         if (have) { setup_tile(to, tt); issue(0, 2); issue_scales((round + 1) & 1); }
-        {
-            const int64_t o_sub = o_cur + wo * 128, t_sub = t_cur + wt * (32 * NBF);
-            const int64_t rows = M - t_sub, cols = O - o_sub;      // <= 0: nothing of this sub-tile exists
-            const bool any = rows > 0 && cols > 0;
-            store_tile<MM::SCALED>(acc, MM::SCALED && any ? s_x + t_sub : s_x,
-                                   reinterpret_cast<const float*>(smem + S_SW_OFF + (round & 1) * SW_BYTES) + wo * 128,
-                                   any ? Y + t_sub * ldy + o_sub : Y, (uint32_t)ldy,
-                                   any ? (int)(rows > 64 ? 64 : rows) : 0, any ? (int)(cols > 128 ? 128 : cols) : 0, smem + wave * EP_WAVE_BYTES);
-        }
+        store_tile<MM::SCALED, 32, false>(acc, sx, reinterpret_cast<const float*>(smem + S_SW_OFF + (round & 1) * SW_BYTES) + wo * 128, Y_sub,
+                                   (uint32_t)ldy, rows_left, cols_left, smem + wave * EP_WAVE_BYTES);
     }
 }
 

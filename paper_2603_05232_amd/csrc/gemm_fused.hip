@@ -11,13 +11,15 @@
 // in the matching window order (fused_window in packed_layout.h).
 //
 // Tile engine.  Persistent workgroups, 256 channels x 256 tokens per tile, 2 x WT wavefronts of 128 channels x
-// (256 / WT) tokens = 4 x NBF accumulator blocks of the 32x32 instruction (WT = 2: four wavefronts, one per SIMD, 256
-// accumulator registers each; WT = 4: eight wavefronts, two per SIMD).  Operands go L2 -> LDS with direct loads into
+// (256 / WT) tokens = 4 x NBF accumulator blocks of the 32x32 instruction.  WT = 4 (eight wavefronts, two per SIMD) is
+// what is built: with WT = 2 (four wavefronts of 128 x 128, a third fewer LDS operand reads) a lone wavefront could not
+// keep its SIMD's matrix pipe busy and the kernel was 7-10 % slower.  Operands go L2 -> LDS with direct loads into
 // two rings: token tiles (32 KB per super-unit, three slots) and packed weights (10 KB per step: 8 KB of stored values
 // + 2 KB of index words, six slots).  The workgroup meets at one barrier per super-unit; a wavefront issues all LDS
 // reads of a step's operands at least one step ahead and the reads of the step before a barrier in that step's first
 // half, so no wait is exposed; the direct loads of later super-units are spread one by one between the matrix
-// instructions.
+// instructions.  The next tile's first operands are requested before the epilogue and waited for inside it, before
+// the first store: the wait counter counts stores too, and a wait behind them would wait for their acknowledgement.
 //
 // Token tile in LDS: 256 rows x 128 bytes, the 16-byte chunk c of row r stored at chunk c ^ ((r >> 1) & 7) (the
 // swizzle is applied on the global-address side: a direct load writes 64 lanes x 16 bytes contiguously, i.e. eight
@@ -31,16 +33,6 @@
 #include "tile_common.h"
 #include "device_info.h"
 #include <type_traits>
-#ifndef SS_EXP_ABURST
-#define SS_EXP_ABURST 0
-#endif
-#ifndef SS_EXP_NOWAIT
-#define SS_EXP_NOWAIT 0
-#endif
-#ifndef SS_EXP_SKIP
-#define SS_EXP_SKIP 0
-#endif
-// timing experiments (wrong results): 1 no token reads, 2 no direct loads, 4 no middle windows, 8 no barrier, 16 no weight reads
 
 namespace ss {
 
@@ -77,7 +69,7 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
     constexpr int IPW = (6 + W - 1) / W;             // 1 KB pieces of index words per wavefront and super-unit (6 per tile: 2 panels x 3 steps; spare turns repeat a piece)
     constexpr int LG = 3 * APS + IPW;                // weight loads per wavefront and super-unit
     constexpr int L = LG + LB;
-    constexpr int PRE_B = W == 4 ? 2 : 1;            // token tiles of the next tile requested before the epilogue (staging takes the other ring slots)
+    constexpr int EP_ROWS = 128 / W;                 // rows per wavefront staged at a time: W x EP_ROWS x 256 B = 32 KB, one ring slot
     static_assert(L <= (3 * NM) / 2, "one direct load behind every second matrix instruction");
     extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
@@ -157,9 +149,9 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
 #pragma unroll
         for (int k = 1; k <= 3; ++k) if (k < nsteps) load_a_step(k, k);
         load_scales(parity);
-        if constexpr (PRE_B == 2) if (U > 1) load_b_unit(1, 1);
+        if (U > 1) load_b_unit(1, 1);
     };
-    uint8_t* const stage = smem + F_B_OFF + (W == 4 ? 2 : 1) * F_BSLOT + wave * EP_WAVE_BYTES;
+    uint8_t* const stage = smem + F_B_OFF + 2 * F_BSLOT + wave * (EP_ROWS * EP_ROWB);
 
     struct Regs { v4i aA[4], a[4], iA, iB, iC; v8i lo[NBF], hi[NBF], al[NBF]; };
 
@@ -171,21 +163,15 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
         zero_acc(acc);
         Regs R;
         auto rd = [&](uint32_t off) -> v4i { return *reinterpret_cast<const v4i*>(smem + off); };
-        // four wavefronts: 256 accumulators per lane, kept in the accumulation half of the register file
-        auto mma = [&](typename MM::acc_t& c, v4i a, const v8i& b, int idx) __attribute__((always_inline)) {
-            if constexpr (W == 4) MM::sparse_agpr(c, a, b, idx);
-            else c = MM::sparse(a, b, c, idx);
-        };
+        auto mma = [&](typename MM::acc_t& c, v4i a, const v8i& b, int idx) __attribute__((always_inline)) { c = MM::sparse(a, b, c, idx); };
         // the four 16-byte reads of token fragment bb's half `hi` (chunks 2 hi, 2 hi + 1 of the lane's 64 bytes)
         auto read_b = [&](v8i& dst, const uint32_t (&vbs)[4], int half, int piece) {
-            if (SS_EXP_SKIP & 1) return;
             const v4i v = rd(vbs[2 * half + piece]);
 #pragma unroll
             for (int e = 0; e < 4; ++e) dst[4 * piece + e] = v[e];
         };
         // middle windows of fragment b's blocks: al[jd], 8-bit: bytes 2..5 of block jd; 16-bit: elements 2..5 of block jd >> 1, half jd & 1
         auto make_al = [&](int b, int jd) {
-            if (SS_EXP_SKIP & 4) return;
             if constexpr (ES == 1) {
                 const int lo_i = 2 * jd;              // registers 2 jd, 2 jd + 1 of the lane's 16
                 const uint32_t x0 = lo_i < 8 ? (uint32_t)R.lo[b][lo_i & 7] : (uint32_t)R.hi[b][lo_i & 7];
@@ -231,22 +217,16 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
             }
             // behind matrix instruction gi (0 .. 3 NM - 1) of the super-unit: direct load number gi / 2 if gi is odd
             auto after = [&](int gi) __attribute__((always_inline)) {
-                if constexpr (MODE == IT_STEADY && !(SS_EXP_SKIP & 2)) {
-#if SS_EXP_ABURST
-                    // weights first, one behind every matrix instruction, then the token tile behind every second one
-                    const int d = gi < LG ? gi : LG + ((gi - LG) >> 1);
-                    if ((gi < LG || ((gi - LG) & 1)) && d < L) {
-#else
+                if constexpr (MODE == IT_STEADY) {
                     const int d = gi >> 1;
                     if ((gi & 1) && d < L) {
-#endif
                         if (d < 3 * APS) {
                             const int jj = d / APS, x = d % APS;
                             const uint32_t so = jj == 0 ? s4 : jj == 1 ? s5 : s6;
-                            if (!(SS_EXP_SKIP & 128)) lds_dma16_at(av + jj * 4096 + x * 1024, lane16, a_wave + so + x * 1024);
+                            lds_dma16_at(av + jj * 4096 + x * 1024, lane16, a_wave + so + x * 1024);
                         } else if (d < LG) {
-                            if (!(SS_EXP_SKIP & 32)) lds_dma16_at(am[d - 3 * APS], lane16, im[d - 3 * APS]);
-                        } else if (!(SS_EXP_SKIP & 64)) {
+                            lds_dma16_at(am[d - 3 * APS], lane16, im[d - 3 * APS]);
+                        } else {
                             const int i = d - LG;
                             lds_dma16_at(bsrc, boff[i < LB ? i : 0], b_ld + i * W * 1024);
                         }
@@ -265,10 +245,8 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
             for (int i = 0; i < NM; ++i) {
                 mma(acc[i / NBF][i % NBF], R.aA[i / NBF], R.lo[i % NBF], R.iA[i / NBF]);
                 __builtin_amdgcn_sched_barrier(0);
-                if (!(SS_EXP_SKIP & 16)) {
                 if (i < 4) R.a[i] = rd(a_now + F_ASTEP + i * 1024);
                 if (i == 4) R.iB = rd(i_now + F_ASTEP);
-                }
                 if (i >= NM / 2) {
 #pragma unroll
                     for (int e = 0; e < 4; ++e) { const int t = (i - NM / 2) * 4 + e; make_al(t / 8, t % 8); }
@@ -282,10 +260,8 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
             for (int i = 0; i < NM; ++i) {
                 mma(acc[i / NBF][i % NBF], R.a[i / NBF], R.hi[i % NBF], R.iB[i / NBF]);
                 __builtin_amdgcn_sched_barrier(0);
-                if (!(SS_EXP_SKIP & 16)) {
                 if (i % NBF == NBF - 1) R.a[i / NBF] = rd(a_now + 2 * F_ASTEP + (i / NBF) * 1024);
                 if (i == 0) R.iC = rd(i_now + 2 * F_ASTEP);
-                }
                 if constexpr (NEXT) {
 #pragma unroll
                     for (int r = 0; r < 2 * NBF; ++r)
@@ -304,7 +280,6 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
 #pragma unroll
                     for (int r = 0; r < 5 + 2 * NBF; ++r)
                         if (mine(r, 5 + 2 * NBF, NM / 2, i)) {
-                            if (r < 5 && (SS_EXP_SKIP & 16)) continue;
                             if (r < 4) R.aA[r] = rd(a_nxt + r * 1024);
                             else if (r == 4) R.iA = rd(i_nxt);
                             else read_b(R.hi[(r - 5) >> 1], vbn[(r - 5) >> 1], 1, (r - 5) & 1);
@@ -316,26 +291,26 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
         };
 
         // ---- tile prologue: the head (requested before the previous epilogue) and the remaining token tiles
-        if (round > 0) wg_barrier();                  // epilogue staging of the previous tile has been read out
-        if constexpr (PRE_B == 1) if (U > 1) load_b_unit(1, 1);
-        if (U > 2) { load_b_unit(2, 2); wait_vm_only<LB>(); } else wait_vm_only<0>();
-        wg_barrier();                                 // head, scales and token tile 1 are published
+        // The head of this tile (requested before the previous epilogue) has landed: every wavefront waited for its
+        // loads inside that epilogue, before its first store.  The first tile waits here.
+        if (round == 0) wait_vm_only<0>();
+        wg_barrier();                                 // head, scales and token tile 1 are published; the epilogue staging has been read out
 #pragma unroll
         for (int f = 0; f < 4; ++f) R.aA[f] = rd(va + f * 1024);
         R.iA = rd(vi);
 #pragma unroll
         for (int r = 0; r < 2 * NBF; ++r) { read_b(R.lo[r >> 1], vb[r >> 1], 0, r & 1); read_b(R.hi[r >> 1], vb[r >> 1], 1, r & 1); }
+        // The first super-unit's direct loads go to the ring slots just read (step 0, token tile 0): every wavefront's
+        // reads must have returned before any of those loads is issued.
+        wait_lgkm0();
+        wg_barrier();
+        if (U > 2) load_b_unit(2, 2);                 // into the ring slot the staging used
 
         int u = 0, par = 0, bn = 1;
         for (; u + 3 < U; ++u) {
             super_unit(std::integral_constant<int, IT_STEADY>{}, u, par, bn);
-#if SS_EXP_NOWAIT
-            wait_lgkm0();
-#else
-            if (SS_EXP_SKIP & (32 | 64 | 128)) wait_vmcnt<0>(); else
             wait_vmcnt<LB>();                          // everything but the token tile just requested has landed; own reads have returned
-#endif
-            if (!(SS_EXP_SKIP & 8)) wg_barrier();
+            wg_barrier();
             par = 3 - par;
             bn = bn == 2 ? 0 : bn + 1;
         }
@@ -346,21 +321,21 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
             par = 3 - par;
             bn = bn == 2 ? 0 : bn + 1;
         }
+        // this sub-tile of Y and its token scales (requested here: they arrive behind the last matrix instructions)
+        const int64_t o_sub = o_blk + wo * 128, t_sub = t_blk + wt * (32 * NBF);
+        const int64_t rows = M - t_sub, cols = O - o_sub;          // <= 0: nothing of this sub-tile exists
+        const bool any = rows > 0 && cols > 0;
+        const int rows_left = any ? (int)(rows > 32 * NBF ? 32 * NBF : rows) : 0, cols_left = any ? (int)(cols > 128 ? 128 : cols) : 0;
+        float sx[NBF];
+        load_token_scales<MM::SCALED>(sx, MM::SCALED && any ? s_x + t_sub : s_x, rows_left);
         super_unit(std::integral_constant<int, IT_LAST>{}, u, par, bn);
-        if constexpr (W == 4) asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 7" ::: "memory");   // the last matrix instructions leave the pipe before their results are read
         wg_barrier();                                 // every wavefront is done with the operand rings
-        const int64_t o_cur = o_blk, t_cur = t_blk;
+        uint16_t* const Y_sub = any ? Y + t_sub * ldy + o_sub : Y;
+        settle(sx);                                   // the token scales have arrived: no wait for them behind the loads requested next
         have = tile_of_round(round + 1, tiles_o, tiles_t, to, tt);
         if (have) { setup_tile(to, tt); request_head((round + 1) & 1); }
-        {
-            const int64_t o_sub = o_cur + wo * 128, t_sub = t_cur + wt * (32 * NBF);
-            const int64_t rows = M - t_sub, cols = O - o_sub;      // <= 0: nothing of this sub-tile exists
-            const bool any = rows > 0 && cols > 0;
-            store_tile<MM::SCALED>(acc, MM::SCALED && any ? s_x + t_sub : s_x,
-                                   reinterpret_cast<const float*>(smem + F_SW_OFF + (round & 1) * F_SWB) + wo * 128,
-                                   any ? Y + t_sub * ldy + o_sub : Y, (uint32_t)ldy,
-                                   any ? (int)(rows > 32 * NBF ? 32 * NBF : rows) : 0, any ? (int)(cols > 128 ? 128 : cols) : 0, stage);
-        }
+        store_tile<MM::SCALED, EP_ROWS, true>(acc, sx, reinterpret_cast<const float*>(smem + F_SW_OFF + (round & 1) * F_SWB) + wo * 128, Y_sub,
+                                        (uint32_t)ldy, rows_left, cols_left, stage);
     }
 }
 
@@ -383,12 +358,6 @@ static ss_status launch_fused(const void* Xq, const float* s_x, const void* w_va
     return launch_status();
 }
 
-static int fused_wt()
-{
-    static const int wt = [] { const char* e = getenv("SS_FUSED_WT"); return e && e[0] == '4' ? 4 : 2; }();
-    return wt;
-}
-
 extern "C" ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M,
                                              int64_t O, int64_t K, int64_t ldx, int N, ss_dtype dtype, void* Y, int64_t ldy, void* stream)
 {
@@ -405,8 +374,7 @@ extern "C" ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, c
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const int U = (int)(K * es / KSTEP);
     const int64_t ldxb = ldx * es;
-#define SS_F(DT) (fused_wt() == 4 ? launch_fused<DT, 4>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, hs) \
-                                  : launch_fused<DT, 2>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, hs))
+#define SS_F(DT) launch_fused<DT, 4>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, hs)
     switch (dtype) {
     case SS_I8: return SS_F(SS_I8);
     case SS_FP8_E4M3: return SS_F(SS_FP8_E4M3);

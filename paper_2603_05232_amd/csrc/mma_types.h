@@ -9,10 +9,6 @@ namespace ss {
 // DENSE_SUB / 2 bytes per lane; lane (row, q) holds the bytes [q DENSE_SUB / 2, (q + 1) DENSE_SUB / 2) of
 // its row within the instruction's k range, for both operands (measured: element e of A lane (i, q)
 // meets element e of B lane (n, q)).
-// sparse_agpr: the same sparse instruction written as assembly with the accumulator pinned to accumulation registers
-// (for kernels whose 256 accumulators fill that half of the register file: the allocator otherwise shuffles whole
-// accumulator blocks between the two halves inside the k loop).  The compiler does not know its latency: results
-// must not be read before the instruction has left the matrix pipe (callers put s_nop's before the epilogue).
 template <int DT> struct Mma;
 template <> struct Mma<SS_I8> {
     typedef v16i acc_t;
@@ -21,7 +17,6 @@ template <> struct Mma<SS_I8> {
     static constexpr int DENSE_SUB = 32;
     static constexpr bool SCALED = true;
     __device__ static acc_t sparse(v4i a, v8i b, acc_t c, int idx) { return __builtin_amdgcn_smfmac_i32_32x32x64_i8(a, b, c, idx, 0, 0); }
-    __device__ static void sparse_agpr(acc_t& c, v4i a, v8i b, int idx) { asm volatile("v_smfmac_i32_32x32x64_i8 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx)); }
     __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c) { return __builtin_amdgcn_mfma_i32_32x32x32_i8(a, b, c, 0, 0, 0); }
 };
 template <> struct Mma<SS_FP8_E4M3> {
@@ -31,7 +26,6 @@ template <> struct Mma<SS_FP8_E4M3> {
     static constexpr int DENSE_SUB = 64;
     static constexpr bool SCALED = true;
     __device__ static acc_t sparse(v4i a, v8i b, acc_t c, int idx) { return __builtin_amdgcn_smfmac_f32_32x32x64_fp8_fp8(a, b, c, idx, 0, 0); }
-    __device__ static void sparse_agpr(acc_t& c, v4i a, v8i b, int idx) { asm volatile("v_smfmac_f32_32x32x64_fp8_fp8 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx)); }
     // format selectors 0 = e4m3 for both operands; block scales 0 = the unscaled form of the instruction
     __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c) { return __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(a, b, c, 0, 0, 0, 0, 0, 0); }
 };
@@ -45,7 +39,6 @@ template <> struct Mma<SS_BF16> {
     {
         return __builtin_amdgcn_smfmac_f32_32x32x32_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v16bf, b), c, idx, 0, 0);
     }
-    __device__ static void sparse_agpr(acc_t& c, v4i a, v8i b, int idx) { asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx)); }
     __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c)
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(v8bf, a), __builtin_bit_cast(v8bf, b), c, 0, 0, 0);
@@ -63,7 +56,6 @@ template <> struct Mma<SS_FP16> {
     {
         return __builtin_amdgcn_smfmac_f32_32x32x32_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v16h, b), c, idx, 0, 0);
     }
-    __device__ static void sparse_agpr(acc_t& c, v4i a, v8i b, int idx) { asm volatile("v_smfmac_f32_32x32x32_f16 %0, %1, %2, %3" : "+a"(c) : "v"(a), "v"(b), "v"(idx)); }
     __device__ static acc_t dense(dfrag_t a, dfrag_t b, acc_t c)
     {
         return __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(v8h, a), __builtin_bit_cast(v8h, b), c, 0, 0, 0);
