@@ -44,7 +44,8 @@ typedef enum {
     SS_ERR_SHAPE = 3,          /* a size is non-positive or violates a divisibility rule      */
     SS_ERR_DTYPE = 4,          /* unknown or unsupported dtype for this call                  */
     SS_ERR_WORKSPACE = 5,      /* workspace pointer not 16-byte aligned                       */
-    SS_ERR_HIP = 6             /* the HIP runtime reported an error at launch                 */
+    SS_ERR_HIP = 6,            /* the HIP runtime reported an error at launch                 */
+    SS_ERR_SCRATCH = 7         /* slide_sparse_gemm_static: the shape needs more scratch than the static buffer holds */
 } ss_status;
 
 /* operand storage type of the GEMM inputs */
@@ -161,6 +162,19 @@ ss_status slide_sparse_gemm_ws(const void* X_lifted, const float* s_x, const voi
 ss_status dense_gemm_ws(const void* Xq, const float* s_x, const void* Wq, const float* s_w,
                         int64_t M, int64_t O, int64_t K, ss_dtype dtype, void* Y, int64_t ldy,
                         void* workspace, size_t workspace_bytes, void* stream);
+
+/* For callers that cannot allocate device memory or pass a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): slide_sparse_gemm_ws with the scratch buffer in a static device array of
+ * slide_static_scratch_bytes() = 16 MiB inside the library (every GPU the library runs on holds its own copy until the
+ * process ends).  The call allocates and frees nothing.  Same arguments, kernels and results as slide_sparse_gemm_ws
+ * given a workspace of slide_gemm_workspace_bytes(); a shape that would need more than the static buffer returns
+ * SS_ERR_SCRATCH and enqueues nothing (16 MiB covers every shape on a device of up to 256 compute units).  All calls on
+ * one GPU share that GPU's array: it holds the previous call's partial sums, every call overwrites the part it reads
+ * (nothing needs clearing), and calls that overlap in time on one GPU (different streams) race on it; order them. */
+size_t slide_static_scratch_bytes(void);
+ss_status slide_sparse_gemm_static(const void* X_lifted, const float* s_x, const void* w_vals,
+                                   const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                                   int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy, void* stream);
 
 /* Fused lifting (Sec. 3.3 lifting operator realised inside the GEMM; the paper fuses it into quantisation, Alg. 1):
  * the same linear layer for the 6:8 pattern (N = 4; any other N returns SS_ERR_BAD_PATTERN_N) computed from the

@@ -21,6 +21,7 @@ EXPORTS = ("slide_lifted_k", "slide_lifted_ld", "slide_packed_sizes", "slide_pru
            "slide_decompose_canonical", "act_lift_quant", "slide_sparse_gemm", "dense_gemm",
            "slide_gemm_workspace_bytes", "slide_sparse_gemm_ws", "dense_gemm_ws",
            "slide_packed_sizes_fused", "slide_decompose_fused", "slide_sparse_gemm_fused",
+           "slide_static_scratch_bytes", "slide_sparse_gemm_static",
            "ss_status_string", "slide_format_version")
 
 _lib = None
@@ -57,6 +58,10 @@ def load():
     lib.slide_packed_sizes_fused.argtypes = [i64, i64, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.slide_decompose_fused.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
     lib.slide_sparse_gemm_fused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, i32, vp, i64, vp]
+    lib.slide_static_scratch_bytes.argtypes = []
+    lib.slide_static_scratch_bytes.restype = sz
+    lib.slide_sparse_gemm_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, i64, vp]
+    lib.slide_sparse_gemm_static.restype = i32
     lib.slide_gemm_workspace_bytes.argtypes = [i64, i64, i64, i32]
     lib.slide_gemm_workspace_bytes.restype = sz
     for name in ("slide_packed_sizes", "slide_prune_quant", "slide_decompose", "slide_decompose_canonical",
@@ -234,4 +239,18 @@ def slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O: int, K: int, N: int
     ldx = Xq.stride(0) if M > 1 else Xq.shape[1]
     _check(load().slide_sparse_gemm_fused(_ptr(Xq), _ptr(s_x), _ptr(w_vals), _ptr(w_meta), _ptr(s_w), M, O, K, ldx, N,
                                           DTYPE_CODE[dtype], _ptr(out), out.stride(0), _stream()), "slide_sparse_gemm_fused")
+    return out
+
+
+def slide_static_scratch_bytes() -> int:
+    return int(load().slide_static_scratch_bytes())
+
+
+def slide_sparse_gemm_static(X_lifted, s_x, w_vals, w_meta, s_w, O: int, dtype: str, out):
+    """slide_sparse_gemm with the split-k scratch in the library's static device array; `out` is required: this call
+    path allocates nothing."""
+    M, Kp = X_lifted.shape
+    assert X_lifted.is_contiguous() and out is not None
+    _check(load().slide_sparse_gemm_static(_ptr(X_lifted), _ptr(s_x), _ptr(w_vals), _ptr(w_meta), _ptr(s_w), M, O, Kp,
+                                           DTYPE_CODE[dtype], _ptr(out), out.stride(0), _stream()), "slide_sparse_gemm_static")
     return out

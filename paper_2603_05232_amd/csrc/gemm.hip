@@ -32,6 +32,7 @@
 #include "lds_pipe.h"
 #include "tile_common.h"
 #include "device_info.h"
+#include <atomic>
 #include <type_traits>
 
 
@@ -563,6 +564,49 @@ extern "C" ss_status slide_sparse_gemm(const void* X_lifted, const float* s_x, c
     return slide_sparse_gemm_ws(X_lifted, s_x, w_vals, w_meta, s_w, M, O, K_lifted, dtype, Y, ldy, nullptr, 0, stream);
 }
 
+// ---- entry point for callers that cannot allocate: the split-k scratch is a static device array ----------------
+// 16 MiB: S k ranges x tiles of 128 x 128 x 4 bytes with S x tiles <= one workgroup per compute unit (256 x 64 KiB).
+constexpr size_t SS_STATIC_SCRATCH_BYTES = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[SS_STATIC_SCRATCH_BYTES];
+
+// Device address of this device's copy of `scratch`, looked up once per device with that device current (in host code
+// the array's name is only a handle for the lookup, never a device address).
+static ss_status static_scratch(void** ptr)
+{
+    static std::atomic<void*> known[MAX_TRACKED_DEVICES];
+    const int d = current_device();
+    if (d < 0 || d >= MAX_TRACKED_DEVICES) return SS_ERR_HIP;
+    void* p = known[d].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return SS_ERR_HIP;
+        known[d].store(p, std::memory_order_release);
+    }
+    *ptr = p;
+    return SS_OK;
+}
+
+extern "C" size_t slide_static_scratch_bytes(void) { return SS_STATIC_SCRATCH_BYTES; }
+
+extern "C" ss_status slide_sparse_gemm_static(const void* X_lifted, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w,
+                                              int64_t M, int64_t O, int64_t K_lifted, ss_dtype dtype, void* Y, int64_t ldy, void* stream)
+{
+    ss_status st = check_gemm(X_lifted, s_x, w_vals, s_w, M, O, K_lifted, dtype, Y, ldy);
+    if (st != SS_OK || M == 0 || O == 0) return st;
+    if (!w_meta) return SS_ERR_NULL;
+    if ((uintptr_t)w_meta & 15) return SS_ERR_SHAPE;
+    // what the shape would use with an unlimited workspace must fit the static array
+    if (slide_gemm_workspace_bytes(M, O, K_lifted, dtype) > SS_STATIC_SCRATCH_BYTES) return SS_ERR_SCRATCH;
+    void* ws = nullptr;
+    st = static_scratch(&ws);
+    if (st != SS_OK) return st;
+    hipStream_t hs = static_cast<hipStream_t>(stream);
+    const int64_t Kpb = K_lifted * elem_size(dtype);
+    const ss_plan p = plan_gemm(M, O, Kpb / KSTEP, SS_STATIC_SCRATCH_BYTES);
+    if (p.path == SS_PATH_SKINNY) return launch_sparse_skinny(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, ws, p.S, hs);
+    if (p.path == SS_PATH_MID) return launch_sparse_mid(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, ws, p.S, hs);
+    return launch_sparse_tile(X_lifted, s_x, w_vals, w_meta, s_w, M, O, Kpb, dtype, Y, ldy, hs);
+}
+
 extern "C" const char* ss_status_string(ss_status s)
 {
     switch (s) {
@@ -573,6 +617,7 @@ extern "C" const char* ss_status_string(ss_status s)
     case SS_ERR_DTYPE: return "unsupported dtype";
     case SS_ERR_WORKSPACE: return "workspace not 16-byte aligned";
     case SS_ERR_HIP: return "HIP runtime error";
+    case SS_ERR_SCRATCH: return "shape needs more scratch memory than the static buffer holds (slide_static_scratch_bytes)";
     }
     return "unknown status";
 }
