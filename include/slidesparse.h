@@ -64,14 +64,16 @@ typedef enum { SS_IN_F32 = 0, SS_IN_BF16 = 1 } ss_act_dtype;
  * outside 1..2^24. */
 int64_t slide_lifted_k(int64_t K, int N);
 
-/* Kld: the width, in elements, of the rows act_lift_quant writes and of the K_lifted argument
+/* Kld (Alg. 1: a lifted row is n_w packed windows = 4 n_w elements; the library stores it padded): the width, in
+ * elements, of the rows act_lift_quant writes and of the K_lifted argument
  * of slide_sparse_gemm: K' rounded up to a whole number of 128-byte units (the k granularity
  * of the GEMM kernels).  Columns K' .. Kld-1 of X_lifted are zero and the matching windows of
  * the packed weights are empty, so they add nothing to the product.  Kld == K' for every
  * benchmark shape of the paper's models at 6:8.  Returns -1 on a bad N, K or dtype. */
 int64_t slide_lifted_ld(int64_t K, int N, ss_dtype dtype);
 
-/* Byte sizes of the two buffers slide_decompose writes for an [O,K] weight matrix.
+/* Byte sizes of the two buffers slide_decompose writes for an [O,K] weight matrix (Sec. 4.3: the compressed
+ * form holds only the non-zeros plus compact index metadata; Sec. 3.4 for the (N-1)/N count).
  * The packed layout is opaque (ordered for the sparse matrix instruction's operand and
  * index registers); rows are padded to a multiple of 128.  With b = bytes per element,
  * vals_bytes = Opad * Kld * b / 2 ((N-1)/N of the dense weight bytes when Kld = K') and
@@ -116,7 +118,7 @@ ss_status slide_decompose_canonical(const void* Wq, int64_t O, int64_t K, int N,
  * per-token quantisation (K' = K rounded up to 4).  An all-zero token gets s_x = 1 and
  * zeros.  Source columns at or beyond K read as zero.  X_lifted is [M, Kld] dense, 16-byte
  * aligned (SS_ERR_SHAPE otherwise), columns K'..Kld-1 zero.  The quantised row is kept in
- * on-chip memory: ceil(K/2N)*2N*sizeof(element) + 8 must not exceed 64 KiB. */
+ * on-chip memory: ceil(K/2N)*2N*sizeof(element) + 72 must not exceed 64 KiB (SS_ERR_SHAPE otherwise). */
 ss_status act_lift_quant(const void* X, ss_act_dtype in_dtype, int64_t M, int64_t K, int64_t ldx,
                          int N, ss_dtype out, void* X_lifted, float* s_x, void* stream);
 
@@ -192,9 +194,11 @@ ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, const void* 
                                   const float* s_w, int64_t M, int64_t O, int64_t K, int64_t ldx, int N,
                                   ss_dtype dtype, void* Y, int64_t ldy, void* stream);
 
+/* Library housekeeping (no passage of the paper): a static, human-readable name for a status code ... */
 const char* ss_status_string(ss_status s);
 
-/* Library / packed-format version (bumped whenever the opaque layout changes). */
+/* ... and the version of the opaque packed layouts (Sec. 4.3 leaves the compressed format to the implementation;
+ * bumped whenever what slide_decompose / slide_decompose_fused write changes). */
 int slide_format_version(void);
 
 #ifdef __cplusplus

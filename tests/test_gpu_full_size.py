@@ -35,6 +35,12 @@ def _run_and_sample(M, K, O, N, dtype, seed, use_workspace=False):
     Yd = binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype, workspace=ws_d)
     assert int(host(viol)[0]) == 0
     assert torch.equal(Y, Y2)                                    # deterministic from launch to launch
+    Yf = None
+    if N == 4 and (K * Xq.element_size()) % 128 == 0:            # the same layer with the lifting applied inside the GEMM
+        fw_vals, fw_meta = binding.slide_decompose_fused(Wq, N, dtype)
+        Yf = binding.slide_sparse_gemm_fused(Xq, s_x2, fw_vals, fw_meta, s_w, O, K, N, dtype)
+        assert torch.equal(Yf, binding.slide_sparse_gemm_fused(Xq, s_x2, fw_vals, fw_meta, s_w, O, K, N, dtype))
+        del fw_vals, fw_meta
     rng = np.random.default_rng(seed + 12345)
     rows = np.sort(rng.choice(M, size=min(M, N_SAMPLE), replace=False))
     cols = np.sort(rng.choice(O, size=min(O, N_SAMPLE), replace=False))
@@ -48,6 +54,12 @@ def _run_and_sample(M, K, O, N, dtype, seed, use_workspace=False):
     assert np.array_equal(from_dev_q(Wq[ci].contiguous(), dtype), ref["Wq"])
     assert np.array_equal(from_dev_q(Xq[ri].contiguous(), dtype), ref["Xq"])
     assert np.array_equal(from_dev_q(XL[ri].contiguous(), dtype), so.lift(ref["Xq"], N))
+    if Yf is not None:                                           # checked here so that every caller covers the fused path
+        if dtype == "i8":
+            assert np.array_equal(sample(Yf), ref["Y"])
+            assert torch.equal(Yf, Yd)
+        else:
+            _float_gemm_check(sample(Yf), ref, dtype)
     return Y, Yd, sample, ref
 
 
@@ -74,7 +86,7 @@ def test_llama3_8b_block_int8_m4096(name, K, O):
 
 @pytest.mark.parametrize("dtype", ["i8", "fp8", "bf16", "fp16"])
 @pytest.mark.parametrize("M", [1, 16, 128])
-@pytest.mark.parametrize("name,K,O", [synth.QWEN25_7B[0], synth.QWEN25_7B[3]])
+@pytest.mark.parametrize("name,K,O", synth.QWEN25_7B)
 def test_qwen25_7b_small_m(dtype, M, name, K, O):
     Y, Yd, sample, ref = _run_and_sample(M, K, O, 4, dtype, seed=M)
     if dtype == "i8":
@@ -86,7 +98,7 @@ def test_qwen25_7b_small_m(dtype, M, name, K, O):
 
 
 @pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
-@pytest.mark.parametrize("name,K,O", [synth.QWEN25_7B[0], synth.QWEN25_7B[3]])
+@pytest.mark.parametrize("name,K,O", synth.QWEN25_7B)
 def test_qwen25_7b_float_m8192(dtype, name, K, O):
     Y, Yd, sample, ref = _run_and_sample(8192, K, O, 4, dtype, seed=7)
     _float_gemm_check(sample(Y), ref, dtype)
@@ -166,3 +178,58 @@ def test_output_offsets_beyond_32_bits(M, ldy_log2):
     buf.zero_()
     binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8", out=buf[:, :O])
     assert np.array_equal(bits16(buf[ri][:, :O].contiguous()), exp)
+
+
+@pytest.mark.parametrize("dtype", ["i8", "fp8"])
+def test_two_persistent_rounds_full_output(dtype):
+    """More 256 x 256 tiles than compute units (17 x 18 = 306: a second persistent round with its tile renumbering, the
+    next tile's first unit requested before the epilogue, scale parity) with ragged edges and a short K, so that the
+    CPU oracle can check EVERY output element of the sparse and of the dense kernel (not one against the other)."""
+    from oracle import gemm_ref
+    N, M, O, K = 4, 4300, 4400, 256
+    rng = np.random.default_rng(11)
+    if dtype == "i8":
+        Wq = rng.integers(-127, 128, size=(O, K)).astype(np.int8)
+        keep = np.argsort(rng.random((O, K // 8, 8)), axis=-1) < rng.integers(0, 7, size=(O, K // 8, 1))
+        Wq = (Wq.reshape(O, K // 8, 8) * keep).reshape(O, K).astype(np.int8)
+        Xq = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+        s_x = rng.uniform(0.01, 0.1, M).astype(np.float32)
+        s_w = rng.uniform(1e-4, 1e-3, O).astype(np.float32)
+        exp = so.epilogue(gemm_ref.gemm_i8_i64(Xq, Wq), s_x, s_w, "i8")
+        w_vals, w_meta = binding.slide_decompose(dev(Wq), N, "i8")
+        Ys = binding.slide_sparse_gemm(dev(so.lift(Xq, N)), dev(s_x), w_vals, w_meta, dev(s_w), O, "i8")
+        assert np.array_equal(bits16(Ys), exp)
+        Yd = binding.dense_gemm(dev(Xq), dev(s_x), dev(Wq), dev(s_w), "i8")
+        assert np.array_equal(bits16(Yd), exp)
+    else:
+        X = synth.activations(M, K, seed=3)
+        W = synth.weights(O, K, seed=3)
+        ref = so.linear_reference(X, W, N, dtype)
+        Wq, s_w = binding.slide_prune_quant(dev(W), N, dtype)
+        w_vals, w_meta = binding.slide_decompose(Wq, N, dtype)
+        XL, s_x = binding.act_lift_quant(dev(X), N, dtype)
+        _float_gemm_check(bits16(binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dtype)), ref, dtype)
+        Xq, s_x2 = binding.act_lift_quant(dev(X), 2, dtype)
+        _float_gemm_check(bits16(binding.dense_gemm(Xq, s_x2, Wq, s_w, dtype)), ref, dtype)
+        fw_vals, fw_meta = binding.slide_decompose_fused(Wq, N, dtype)
+        _float_gemm_check(bits16(binding.slide_sparse_gemm_fused(Xq, s_x2, fw_vals, fw_meta, s_w, O, K, N, dtype)), ref, dtype)
+
+
+def test_documented_limits():
+    """Limits the header states: act_lift_quant keeps the quantised row in 64 KiB of LDS; dense_gemm wants whole
+    128-byte rows while the sparse side pads ragged K itself."""
+    x = torch.zeros((2, 65536), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(binding.SlideSparseError) as e:
+        binding.act_lift_quant(x, 4, "i8")                                   # 65536 + 8 bytes of quantised row
+    assert e.value.code == 3
+    binding.act_lift_quant(x[:, :65536 - 128], 4, "i8")                      # just below the limit
+    Xq = torch.zeros((4, 200), dtype=torch.int8, device="cuda:0")
+    Wq = torch.zeros((128, 200), dtype=torch.int8, device="cuda:0")
+    s = torch.ones((128,), dtype=torch.float32, device="cuda:0")
+    with pytest.raises(binding.SlideSparseError) as e:
+        binding.dense_gemm(Xq, s[:4], Wq, s, "i8")                           # K = 200 bytes is not a multiple of 128
+    assert e.value.code == 3
+    w_vals, w_meta = binding.slide_decompose(Wq, 4, "i8")                    # the sparse side pads K' = 300 to 384
+    XL, s_x = binding.act_lift_quant(torch.zeros((4, 200), dtype=torch.float32, device="cuda:0"), 4, "i8")
+    assert XL.shape[1] == 384
+    assert not bool(binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s, 128, "i8").any())
