@@ -56,7 +56,8 @@ def parse():
     ap.add_argument("--sweep", choices=["dtypes_m", "mid_m", "patterns", "llama_block"], default=None,
                     help="instead of the headline step, time one of the other benchmark configurations and print its table "
                          "as one JSON line: dtypes_m = INT8/FP8/BF16 at M in {1,16,128,8192} on the Qwen2.5-7B shapes; "
-                         "mid_m = INT8 at M in {64..2048}; patterns = 4:6, 6:8, 8:10 at M=8192 INT8; llama_block = Llama-3-8B linears at M=4096, 6:8 INT8")
+                         "mid_m = INT8 at M in {64..2048}; patterns = 4:6, 6:8, 8:10 at M=8192 INT8; llama_block = a Llama-3-8B-shaped block "
+                         "forward at M=4096, 6:8 INT8, the four linears chained through torch reference attention / RMSNorm")
     ap.add_argument("--graph", action="store_true",
                     help="sweeps only: time replays of a HIP graph holding the launches instead of eager calls from Python (below "
                          "about 10 us per kernel the binding's call overhead is otherwise part of the figure)")
@@ -95,8 +96,54 @@ def cpu_baseline(layers, n_tok, n_ch):
             "seconds": dt}
 
 
+def block_sweep(args, torch, synth, dev):
+    """Llama-3-8B-shaped block forward at M = 4096, 6:8 INT8: the four linears chained through torch reference RMSNorm /
+    attention / gating (not timed); per linear the quantiser and the GEMM are timed with HIP events inside the chained
+    forward, and the sums over the four linears are compared (model mode, Sec. 5 / App. D.3)."""
+    from paper_2603_05232_amd.block import LlamaBlock, HIDDEN
+    M = 4096
+    blk = LlamaBlock(dev)
+    x = torch.from_numpy(synth.activations(M, HIDDEN, seed=5)).to(dev).to(torch.bfloat16)
+    out = {"sweep": "llama_block", "tokens": M, "pattern": "6:8", "dtype": "i8", "steps": args.steps, "warmup": args.warmup,
+           "timing": "HIP events around the quantiser and the GEMM of each linear inside the chained block forward; attention, "
+                     "RMSNorm, gating and residuals are torch reference ops between them and are not counted",
+           "paths": {}}
+    for path in ("fused", "lifted", "dense"):
+        for _ in range(args.warmup):
+            blk.forward(x, path)
+        acc = {name: [0.0, 0.0] for name, _, _ in synth.LLAMA3_8B}
+        for _ in range(args.steps):
+            evs = {}
+
+            def timer(name, stage):
+                e = torch.cuda.Event(enable_timing=True)
+                e.record()
+                evs[(name, stage)] = e
+            blk.forward(x, path, timer)
+            torch.cuda.synchronize()
+            for name in acc:
+                acc[name][0] += evs[(name, "start")].elapsed_time(evs[(name, "quantised")])
+                acc[name][1] += evs[(name, "quantised")].elapsed_time(evs[(name, "done")])
+        per = {name: {"quant_ms": q / args.steps, "gemm_ms": g / args.steps} for name, (q, g) in acc.items()}
+        out["paths"][path] = {"per_linear": per, "sum_quant_ms": sum(v["quant_ms"] for v in per.values()),
+                              "sum_gemm_ms": sum(v["gemm_ms"] for v in per.values())}
+    P = out["paths"]
+    tot = lambda p: P[p]["sum_quant_ms"] + P[p]["sum_gemm_ms"]
+    hw_ops = sum(2.0 * M * O * K * 1.5 for _, K, O in synth.LLAMA3_8B)
+    out.update({"linear_time_ms": {p: tot(p) for p in P},
+                "speedup_linears_fused_vs_dense": tot("dense") / tot("fused"),
+                "speedup_linears_lifted_vs_dense": tot("dense") / tot("lifted"),
+                "speedup_gemm_fused_vs_dense": P["dense"]["sum_gemm_ms"] / P["fused"]["sum_gemm_ms"],
+                "speedup_gemm_lifted_vs_dense": P["dense"]["sum_gemm_ms"] / P["lifted"]["sum_gemm_ms"],
+                "fused_gemm_frac_of_sparse_peak": hw_ops / (P["fused"]["sum_gemm_ms"] * 1e-3) * 1e-12 / PEAK_INT8_SPARSE_TOPS,
+                "speedup_bound_N_over_N_minus_1": 4.0 / 3.0})
+    print(json.dumps(out))
+
+
 def sweep(args, torch, binding, synth, dev):
     """Times lift + sparse GEMM against quantise + dense GEMM for every case of one configuration."""
+    if args.sweep == "llama_block":
+        return block_sweep(args, torch, synth, dev)
     if args.sweep == "dtypes_m":
         cases = [(dt, M, 4, name, K, O) for dt in ("i8", "fp8", "bf16") for M in (1, 16, 128, 8192) for name, K, O in synth.QWEN25_7B]
     elif args.sweep == "mid_m":
@@ -104,7 +151,7 @@ def sweep(args, torch, binding, synth, dev):
     elif args.sweep == "patterns":
         cases = [("i8", 8192, N, f"{2 * N - 2}:{2 * N}", K, O) for N, K, O in synth.PATTERN_SWEEP]
     else:
-        cases = [("i8", 4096, 4, name, K, O) for name, K, O in synth.LLAMA3_8B]
+        raise ValueError(args.sweep)
     esize = {"i8": 1, "fp8": 1, "bf16": 2}
     peak = {"i8": PEAK_INT8_DENSE_TOPS, "fp8": PEAK_INT8_DENSE_TOPS, "bf16": PEAK_INT8_DENSE_TOPS / 2}
     rows = []
