@@ -108,6 +108,37 @@ __global__ __launch_bounds__(THREADS) void k_act_lift_quant(const TIN* __restric
         if (t == 0) s_x[m] = s;
     }
 
+    // ---- N = 2 from registers: plain quantisation has no windows to gather, so the quantised vectors go straight to
+    // global memory (4 or 8 bytes per lane, contiguous across the wavefront) without the round trip through LDS
+    if constexpr (MAXV > 0) {
+        if (N == 2) {
+            constexpr int OW = IV::N * ES / 4;           // output dwords per input vector: 1 (fp32 -> 8 bit), 2, 2 or 4
+            uint32_t* out32 = reinterpret_cast<uint32_t*>(XL + m * (int64_t)Kp * ES);
+#pragma unroll
+            for (int i = 0; i < MAXV; ++i) {
+                const int idx = t + i * THREADS;
+                if (idx < nvec) {
+                    float f[IV::N]; IV::unpack(v[i], f);
+                    uint32_t w[OW];
+#pragma unroll
+                    for (int k = 0; k < OW; ++k) {
+                        if constexpr (ES == 1)
+                            w[k] = quant1<OUT>(f[4 * k], r) | (quant1<OUT>(f[4 * k + 1], r) << 8) | (quant1<OUT>(f[4 * k + 2], r) << 16) |
+                                   (quant1<OUT>(f[4 * k + 3], r) << 24);
+                        else
+                            w[k] = quant1<OUT>(f[2 * k], r) | (quant1<OUT>(f[2 * k + 1], r) << 16);
+                    }
+                    if constexpr (OW == 1) out32[idx] = w[0];
+                    else if constexpr (OW == 2) reinterpret_cast<uint2*>(out32)[idx] = make_uint2(w[0], w[1]);
+                    else reinterpret_cast<uint4*>(out32)[idx] = make_uint4(w[0], w[1], w[2], w[3]);
+                }
+            }
+            // zero padding of the stored width (K is a whole number of vectors here, so of dwords too)
+            for (int k = K * ES / 4 + t; k < Kp * ES / 4; k += THREADS) out32[k] = 0u;
+            return;
+        }
+    }
+
     // ---- pass 2a: quantise every source element once, into LDS
     if constexpr (MAXV > 0) {
 #pragma unroll
