@@ -19,10 +19,15 @@
 #include "packed_layout.h"
 #include "mma_types.h"
 #include "device_info.h"
+#include <cstdlib>
 
 namespace ss {
 
 // wavefronts per workgroup: 4, or 8 when there are fewer workgroups than compute units (more load streams per unit)
+
+// units a wavefront keeps in flight in registers: 4 where a workgroup is a single fragment (few workgroups, each
+// wavefront a chain of load round trips), 2 where it holds several fragments (many workgroups per compute unit)
+template <int FPW, int TB> constexpr int SK_DEPTH = FPW == 1 ? (TB == 1 ? 4 : 3) : 2;
 
 template <typename ACC> __device__ inline void sk_zero(ACC& a)
 {
@@ -130,11 +135,15 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
     const v4i* av = reinterpret_cast<const v4i*>(w_vals) + (panel * 2 * U * FRAGS_PER_PANEL + f0) * 64 + lane;
     const int* am = reinterpret_cast<const int*>(w_meta) + (panel * 2 * U * 64 + lane) * FRAGS_PER_PANEL + f0;
     // token rows: lane (n, qb) holds the lifted bytes [32 qb, 32 qb + 32) of token n within a step
+    // Lanes whose token does not exist load nothing (their products are never stored): a load instruction costs the
+    // memory pipeline by its active lanes, and with a single token 31 of 32 would fetch copies.
     const uint8_t* xb[TB];
+    bool live[TB];
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
         int64_t tok = tb * 32 + (lane & 31);
-        tok = tok < M ? tok : M - 1;
+        live[tb] = tok < M;
+        tok = live[tb] ? tok : M - 1;
         xb[tb] = XL + tok * Kpb + 32 * (lane >> 5);
     }
     auto load = [&](SkSparseUnit<TB, FPW>& R, int u) {
@@ -149,35 +158,54 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
 #pragma unroll
                 for (int f = 0; f < FPW; ++f) R.idx[h][f] = w[f];
             }
-#pragma unroll
-            for (int tb = 0; tb < TB; ++tb) {
-                const v4i* p = reinterpret_cast<const v4i*>(xb[tb] + s * FRAG_KB);
-                R.b[tb][2 * h] = p[0];
-                R.b[tb][2 * h + 1] = p[1];
-            }
         }
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb)
+            if (live[tb]) {
+#pragma unroll
+                for (int h = 0; h < 2; ++h) {
+                    const v4i* p = reinterpret_cast<const v4i*>(xb[tb] + (2 * (int64_t)u + h) * FRAG_KB);
+                    R.b[tb][2 * h] = p[0];
+                    R.b[tb][2 * h + 1] = p[1];
+                }
+            }
     };
     typename MM::acc_t acc[FPW * TB];
 #pragma unroll
     for (int i = 0; i < FPW * TB; ++i) sk_zero(acc[i]);
-    SkSparseUnit<TB, FPW> cur, nxt;
+    // A wavefront's units go through a ring of D register stages, all of them in flight: a lone wavefront's chain of
+    // load round trips (a few units, each a trip to HBM) is what bounds the kernel where workgroups are single fragments.
+    constexpr int D = SK_DEPTH<FPW, TB>;
+    SkSparseUnit<TB, FPW> st[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) st[d].b[tb][j] = v4i{0, 0, 0, 0};     // lanes without a token keep zeros
     // k range of this workgroup: units [u, u_end) of U; gridDim.y ranges
     const int u_end = (int)((int64_t)(blockIdx.y + 1) * U / gridDim.y);
-    int u = (int)((int64_t)blockIdx.y * U / gridDim.y) + wave;
-    if (u < u_end) load(cur, u);
-    for (; u < u_end; u += SK_WAVES) {
-        const bool more = u + SK_WAVES < u_end;
-        if (more) load(nxt, u + SK_WAVES);
+    const int u0 = (int)((int64_t)blockIdx.y * U / gridDim.y) + wave;
 #pragma unroll
-        for (int h = 0; h < 2; ++h)
+    for (int d = 0; d < D; ++d)
+        if (u0 + d * SK_WAVES < u_end) load(st[d], u0 + d * SK_WAVES);
+    for (int u = u0; u < u_end; u += D * SK_WAVES) {
 #pragma unroll
-            for (int tb = 0; tb < TB; ++tb) {
-                const v4i lo = cur.b[tb][2 * h], hi = cur.b[tb][2 * h + 1];
-                const v8i b = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        for (int d = 0; d < D; ++d) {
+            const int uu = u + d * SK_WAVES;
+            if (uu < u_end) {
 #pragma unroll
-                for (int f = 0; f < FPW; ++f) acc[f * TB + tb] = MM::sparse(cur.a[h][f], b, acc[f * TB + tb], cur.idx[h][f]);
+                for (int h = 0; h < 2; ++h)
+#pragma unroll
+                    for (int tb = 0; tb < TB; ++tb) {
+                        const v4i lo = st[d].b[tb][2 * h], hi = st[d].b[tb][2 * h + 1];
+                        const v8i b = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+#pragma unroll
+                        for (int f = 0; f < FPW; ++f) acc[f * TB + tb] = MM::sparse(st[d].a[h][f], b, acc[f * TB + tb], st[d].idx[h][f]);
+                    }
+                if (uu + D * SK_WAVES < u_end) load(st[d], uu + D * SK_WAVES);
             }
-        if (more) cur = nxt;
+        }
     }
     sk_reduce<SK_WAVES, typename MM::acc_t, FPW * TB>(acc, red, wave, lane);
     if (wave == 0) {
@@ -230,10 +258,12 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* _
     const int frow = sk_frag_row(lane & 31), q = lane >> 5;
     // token rows: lane (n, q) holds bytes [q SUB / 2, (q + 1) SUB / 2) of token n within an instruction's k range
     const uint8_t* xb[TB];
+    bool live[TB];                                       // lanes without a token load nothing (see the sparse kernel)
 #pragma unroll
     for (int tb = 0; tb < TB; ++tb) {
         int64_t tok = tb * 32 + (lane & 31);
-        tok = tok < M ? tok : M - 1;
+        live[tb] = tok < M;
+        tok = live[tb] ? tok : M - 1;
         xb[tb] = Xq + tok * Kb + (SUB / 2) * q;
     }
     auto load = [&](SkDenseUnit<TB, FPW>& R, int u) {
@@ -243,23 +273,37 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* _
             for (int j = 0; j < 4; ++j) R.a[f][j] = *reinterpret_cast<const v4i*>(wp[f][j] + (int64_t)u * 128);
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb)
+            if (live[tb]) {
 #pragma unroll
-            for (int t = 0; t < NSUB; ++t)
+                for (int t = 0; t < NSUB; ++t)
 #pragma unroll
-                for (int piece = 0; piece < RPF; ++piece)
-                    R.b[tb][t * RPF + piece] = *reinterpret_cast<const v4i*>(xb[tb] + (int64_t)u * 128 + t * SUB + 16 * piece);
+                    for (int piece = 0; piece < RPF; ++piece)
+                        R.b[tb][t * RPF + piece] = *reinterpret_cast<const v4i*>(xb[tb] + (int64_t)u * 128 + t * SUB + 16 * piece);
+            }
     };
     typename MM::acc_t acc[FPW * TB];
 #pragma unroll
     for (int i = 0; i < FPW * TB; ++i) sk_zero(acc[i]);
-    SkDenseUnit<TB, FPW> cur, nxt;
+    constexpr int D = SK_DEPTH<FPW, TB>;                     // register stages in flight per wavefront (see the sparse kernel)
+    SkDenseUnit<TB, FPW> st[D];
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+#pragma unroll
+        for (int tb = 0; tb < TB; ++tb)
+#pragma unroll
+            for (int j = 0; j < 4; ++j) st[d].b[tb][j] = v4i{0, 0, 0, 0};
     uint8_t* my = tile[wave];
     const int u_end = (int)((int64_t)(blockIdx.y + 1) * U / gridDim.y);
-    int u = (int)((int64_t)blockIdx.y * U / gridDim.y) + wave;
-    if (u < u_end) load(cur, u);
-    for (; u < u_end; u += SK_WAVES) {
-        const bool more = u + SK_WAVES < u_end;
-        if (more) load(nxt, u + SK_WAVES);
+    const int u0 = (int)((int64_t)blockIdx.y * U / gridDim.y) + wave;
+#pragma unroll
+    for (int d = 0; d < D; ++d)
+        if (u0 + d * SK_WAVES < u_end) load(st[d], u0 + d * SK_WAVES);
+    for (int ub = u0; ub < u_end; ub += D * SK_WAVES) {
+#pragma unroll
+      for (int d = 0; d < D; ++d) {
+        const int u = ub + d * SK_WAVES;
+        if (u >= u_end) continue;
+        SkDenseUnit<TB, FPW>& cur = st[d];
         // lines -> wavefront-private LDS tile -> fragments (LDS operations of one wavefront execute in order)
 #pragma unroll
         for (int f = 0; f < FPW; ++f)
@@ -288,7 +332,8 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* _
                 for (int tb = 0; tb < TB; ++tb) acc[f * TB + tb] = MM::dense(a, b[tb], acc[f * TB + tb]);
             }
         }
-        if (more) cur = nxt;
+        if (u + D * SK_WAVES < u_end) load(cur, u + D * SK_WAVES);
+      }
     }
     sk_reduce<SK_WAVES, typename MM::acc_t, FPW * TB>(acc, red, wave, lane);
     if (wave == 0) {
@@ -358,9 +403,15 @@ static ss_status launch_sparse_one(const void* XL, const float* s_x, const void*
         if (first != SS_OK || S <= 1) return first;
         hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
                            static_cast<uint16_t*>(Y), ldy);
-    } else
-        hipLaunchKernelGGL((k_sparse_skinny<DT, TB, FPW, 4>), dim3(grid), dim3(256), 0, stream, static_cast<const uint8_t*>(XL), s_x,
+    } else {
+        // several fragments per workgroup; with S > 1 the k range is split over S workgroups per fragment group
+        hipLaunchKernelGGL((k_sparse_skinny<DT, TB, FPW, 4>), dim3(grid, (unsigned)S), dim3(256), 0, stream, static_cast<const uint8_t*>(XL), s_x,
                            static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy, ws);
+        const ss_status first = launch_status();
+        if (first != SS_OK || S <= 1) return first;
+        hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3((unsigned)(npanels * FRAGS_PER_PANEL)), dim3(64 * TB), 0, stream,
+                           static_cast<const v4i*>(ws), S, s_x, s_w, M, O, static_cast<uint16_t*>(Y), ldy);
+    }
     return launch_status();
 }
 
@@ -382,15 +433,49 @@ static ss_status launch_dense_one(const void* Xq, const float* s_x, const void* 
     return launch_status();
 }
 
-// token blocks of 32: 1 (M <= 32) or 2 (M <= 64).  S > 1 only arrives where skinny_splits() allows it: fewer fragments
-// than compute units, hence single-fragment workgroups of eight wavefronts.
+// k ranges when workgroups are single 32-channel fragments (fewer fragments, counted in whole panels, than compute
+// units; eight wavefronts each): every wavefront keeps at least eight units, at most `cap` ranges.  Measured on
+// 18944 -> 3584 (112 fragments, INT8 6:8): M = 16 28 -> 20 us, M = 32 37 -> 24 us; at M = 1 the second kernel costs
+// what the split saves, so fewer than 8 tokens are not split.
+static int frag_splits(int64_t M, int64_t O, int64_t units, int cap)
+{
+    const int64_t nfrag = (O + PANEL - 1) / PANEL * FRAGS_PER_PANEL;
+    const int cus = cu_count();
+    if (M < 8 || nfrag >= cus) return 1;
+    int64_t S = cus / nfrag;
+    if (S > units / 64) S = units / 64;
+    if (S > cap) S = cap;
+    return S < 2 ? 1 : (int)S;
+}
+
+// k ranges when workgroups are whole 128-channel panels (sparse kernel, rows of at least 64 units on fewer panels than
+// compute units): one workgroup per compute unit, ranges of at least 32 units.  Measured on 18944 -> 3584 (28 panels,
+// INT8 6:8; single fragments unsplit -> panels in 4..7 ranges): M = 1 19 -> 16 us, M = 16 28 -> 17 us, M = 32 37 -> 19 us;
+// on rows of 42 units (3584 -> 4608) the second kernel costs more than the split saves.
+static int panel_splits(int64_t O, int64_t units, int cap)
+{
+    const int64_t npanels = (O + PANEL - 1) / PANEL;
+    const int cus = cu_count();
+    if (npanels >= cus) return 1;
+    int64_t S = cus / npanels;
+    if (S > units / 32) S = units / 32;
+    if (S > cap) S = cap;
+    return S < 2 ? 1 : (int)S;
+}
+
+// token blocks of 32: 1 (M <= 32) or 2 (M <= 64).  S = the ranges the workspace has room for.
 template <int DT>
 static ss_status launch_sparse_dt(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
                                   int64_t Kpb, void* Y, int64_t ldy, void* ws, int S, hipStream_t st)
 {
     const int64_t frags = (O + PANEL - 1) / PANEL * FRAGS_PER_PANEL;
-    const int fpw = pick_fpw(frags);
-#define SS_GO(TB, FPW) return launch_sparse_one<DT, TB, FPW>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, FPW == 1 ? S : 1, st)
+    int fpw = pick_fpw(frags);
+    // Long rows on few panels: whole panels per workgroup (the token rows are read once per 128 channels instead of once
+    // per 32) with the k range split over enough workgroups to fill the chip; otherwise S only applies to single fragments.
+    const int s4 = panel_splits(O, Kpb / KSTEP, S);
+    int s_use = fpw == 1 ? frag_splits(M, O, Kpb / KSTEP, S) : 1;
+    if (s4 > 1) { fpw = 4; s_use = s4; }
+#define SS_GO(TB, FPW) return launch_sparse_one<DT, TB, FPW>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, s_use, st)
     if (M <= 32) { if (fpw == 4) SS_GO(1, 4); if (fpw == 2) SS_GO(1, 2); SS_GO(1, 1); }
     if (fpw == 4) SS_GO(2, 4);
     if (fpw == 2) SS_GO(2, 2);
@@ -404,28 +489,24 @@ static ss_status launch_dense_dt(const void* Xq, const float* s_x, const void* W
 {
     // One fragment per workgroup: the dense kernel stages its weight lines through LDS, and more fragments per
     // workgroup cost more in occupancy than they save in token re-reads (measured: 21 vs 35 us on 3584 -> 37888).
-    if (M <= 32) return launch_dense_one<DT, 1, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, st);
-    return launch_dense_one<DT, 2, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, st);
+    const int s_use = frag_splits(M, O, Kb / KSTEP, S);
+    if (M <= 32) return launch_dense_one<DT, 1, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, s_use, st);
+    return launch_dense_one<DT, 2, 1>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, s_use, st);
 }
 
 // Host side, called by the C entry points for M <= SS_SKINNY_MAX_M.  Arguments are already validated.
 namespace ss {
 
-// Number of k ranges for the few-token kernels: only where the 32-channel fragments (counted in whole panels, as
-// the sparse kernel launches them) are fewer than the compute units, so that workgroups are single fragments of
-// eight wavefronts; every wavefront keeps at least eight units; no more than the workspace holds.  Measured on
-// 18944 -> 3584 (112 fragments, INT8 6:8): M = 16 28 -> 20 us, M = 32 37 -> 24 us; at M = 1 the second kernel
-// costs what the split saves (19 us either way), so fewer than 8 tokens are not split.
+// Number of k ranges the few-token kernels may use with a workspace of ws_bytes: the larger of what the two split
+// policies above would take (the launchers apply their own policy below this bound).
 int skinny_splits(int64_t M, int64_t O, int64_t units, size_t ws_bytes)
 {
-    const int64_t nfrag = (O + PANEL - 1) / PANEL * FRAGS_PER_PANEL;
-    const int cus = cu_count();
-    if (M < 8 || M > SS_SKINNY_MAX_M || nfrag >= cus) return 1;
-    int64_t S = cus / nfrag;
-    if (S > units / 64) S = units / 64;
-    const int64_t fit = (int64_t)(ws_bytes / skinny_workspace_bytes(M, O, 2) * 2);
-    if (S > fit) S = fit;
-    return S < 2 ? 1 : (int)S;
+    if (M > SS_SKINNY_MAX_M) return 1;
+    const size_t per_range = skinny_workspace_bytes(M, O, 2) / 2;
+    const int64_t fit = (int64_t)(ws_bytes / per_range);
+    const int cap = fit > 64 ? 64 : (int)fit;
+    const int a = frag_splits(M, O, units, cap), b = panel_splits(O, units, cap);
+    return a > b ? a : b;
 }
 
 size_t skinny_workspace_bytes(int64_t M, int64_t O, int S)

@@ -57,7 +57,8 @@ def test_gemm_workspace_bytes(lib):
     # 64 KiB (128 x 128 partial sums of 4 bytes) per tile and k range; 0 where the k range is not split
     w = binding.slide_gemm_workspace_bytes
     assert w(16, 4608, 5376, "i8") == 0                       # few tokens: weights streamed once
-    assert w(16, 3584, 28416, "i8") == 2 * 112 * 4096 and w(1, 3584, 28416, "i8") == 0   # ... long rows, few fragments: two ranges
+    # ... long rows on few panels (28 panels of 128 channels, 222 units): whole panels in 6 k ranges, also for one token
+    assert w(16, 3584, 28416, "i8") == 6 * 112 * 4096 and w(1, 3584, 28416, "i8") == 6 * 112 * 4096
     assert w(8192, 4608, 5376, "i8") == 0                     # enough 256 x 256 tiles
     assert w(128, 4608, 5376, "i8") % (36 * 65536) == 0 and w(128, 4608, 5376, "i8") > 0
     assert w(256, 3584, 28416, "i8") % (56 * 65536) == 0 and w(256, 3584, 28416, "i8") > 0
