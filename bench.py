@@ -29,7 +29,7 @@ PEAK_HBM_GBS = 8000.0
 # constant, not measured by the run that prints it.  It comes from the FETCH_SIZE and WRITE_SIZE counters of two
 # rocprofv3 --pmc runs of this script, each scaled by what the same counter reads for the 256 MiB elementwise copy of
 # --copy-calibration; summary and commands in profiles/gemm_qwen7b_m8192_int8_hbm_traffic.txt.
-RECORDED_TRAFFIC = {"fused": None, "lifted": 1.2853e9}
+RECORDED_TRAFFIC = {"fused": 1.0481e9, "lifted": 1.2935e9}
 N_PATTERN = 4                      # 6:8
 M_TOKENS = 8192
 
@@ -168,10 +168,14 @@ def sweep(args, torch, binding, synth, dev):
         # scratch for the shapes whose k range is split over workgroups (0 bytes where it is not)
         ws_bytes = (binding.slide_gemm_workspace_bytes(M, O, XL.shape[1], dt), binding.slide_gemm_workspace_bytes(M, O, K, dt))
         ws_s, ws_d = (torch.empty((n,), dtype=torch.uint8, device=dev) if n else None for n in ws_bytes)
+        fused_ok = N == 4 and (K * esize[dt]) % 128 == 0      # the fused kernel's documented domain
         fns = {"lift": lambda: binding.act_lift_quant(X, N, dt, out=XL, s_x=s_x),
                "sparse": lambda: binding.slide_sparse_gemm(XL, s_x, w_vals, w_meta, s_w, O, dt, out=Y, workspace=ws_s),
                "quant": lambda: binding.act_lift_quant(X, 2, dt, out=Xq, s_x=s_xd),
                "dense": lambda: binding.dense_gemm(Xq, s_xd, Wq, s_w, dt, out=Y, workspace=ws_d)}
+        if fused_ok:
+            fw_vals, fw_meta = binding.slide_decompose_fused(Wq, N, dt)
+            fns["fused"] = lambda: binding.slide_sparse_gemm_fused(Xq, s_xd, fw_vals, fw_meta, s_w, O, K, N, dt, out=Y)
         t = {}
         for k, fn in fns.items():
             for _ in range(args.warmup):
@@ -198,6 +202,8 @@ def sweep(args, torch, binding, synth, dev):
         sparse_bytes = O * Kp * b * 0.625 + M * Kp * b + 2 * M * O     # packed weights + lifted tokens + output
         rows.append({"dtype": dt, "M": M, "pattern": f"{2 * N - 2}:{2 * N}", "layer": name, "K": K, "O": O, "K_lifted": Kp,
                      "lift_ms": t["lift"], "sparse_gemm_ms": t["sparse"], "quant_ms": t["quant"], "dense_gemm_ms": t["dense"],
+                     "fused_gemm_ms": t.get("fused"), "fused_gemm_speedup": t["dense"] / t["fused"] if fused_ok else None,
+                     "fused_layer_speedup": (t["quant"] + t["dense"]) / (t["quant"] + t["fused"]) if fused_ok else None,
                      "gemm_speedup": t["dense"] / t["sparse"], "layer_speedup": (t["quant"] + t["dense"]) / (t["lift"] + t["sparse"]),
                      "sparse_frac_of_sparse_peak": 2.0 * M * O * Kp / (t["sparse"] * 1e-3) * 1e-12 / (2 * peak[dt]),
                      "dense_frac_of_dense_peak": 2.0 * M * O * K / (t["dense"] * 1e-3) * 1e-12 / peak[dt],
