@@ -175,7 +175,8 @@ def sweep(args, torch, binding, synth, dev):
                "dense": lambda: binding.dense_gemm(Xq, s_xd, Wq, s_w, dt, out=Y, workspace=ws_d)}
         if fused_ok:
             fw_vals, fw_meta = binding.slide_decompose_fused(Wq, N, dt)
-            fns["fused"] = lambda: binding.slide_sparse_gemm_fused(Xq, s_xd, fw_vals, fw_meta, s_w, O, K, N, dt, out=Y)
+            ws_f = torch.empty((ws_bytes[1],), dtype=torch.uint8, device=dev) if ws_bytes[1] else None      # same size rule as the dense GEMM
+            fns["fused"] = lambda: binding.slide_sparse_gemm_fused(Xq, s_xd, fw_vals, fw_meta, s_w, O, K, N, dt, out=Y, workspace=ws_f)
         t = {}
         for k, fn in fns.items():
             for _ in range(args.warmup):

@@ -193,6 +193,15 @@ ss_status slide_decompose_fused(const void* Wq, int64_t O, int64_t K, int N, ss_
 ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta,
                                   const float* s_w, int64_t M, int64_t O, int64_t K, int64_t ldx, int N,
                                   ss_dtype dtype, void* Y, int64_t ldy, void* stream);
+/* The fused GEMM with a caller-owned scratch buffer, as slide_sparse_gemm_ws (Sec. 5's token counts from decode to
+ * prefill): for few tokens and for shapes with few tiles the same kernel families as the other GEMMs are used, with
+ * the k loop counted in units of 128 unlifted bytes, and a workspace of slide_gemm_workspace_bytes(M, O, K, dtype)
+ * bytes (K the unlifted row length, as for dense_gemm_ws) lets them split the k range.  workspace rules and error
+ * behaviour as for slide_sparse_gemm_ws; slide_sparse_gemm_fused is this call without workspace. */
+ss_status slide_sparse_gemm_fused_ws(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta,
+                                     const float* s_w, int64_t M, int64_t O, int64_t K, int64_t ldx, int N,
+                                     ss_dtype dtype, void* Y, int64_t ldy, void* workspace, size_t workspace_bytes,
+                                     void* stream);
 
 /* Library housekeeping (no passage of the paper): a static, human-readable name for a status code ... */
 const char* ss_status_string(ss_status s);

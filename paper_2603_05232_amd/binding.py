@@ -20,7 +20,7 @@ DTYPE_CODE = {"i8": SS_I8, "fp8": SS_FP8_E4M3, "bf16": SS_BF16, "fp16": SS_FP16}
 EXPORTS = ("slide_lifted_k", "slide_lifted_ld", "slide_packed_sizes", "slide_prune_quant", "slide_decompose",
            "slide_decompose_canonical", "act_lift_quant", "slide_sparse_gemm", "dense_gemm",
            "slide_gemm_workspace_bytes", "slide_sparse_gemm_ws", "dense_gemm_ws",
-           "slide_packed_sizes_fused", "slide_decompose_fused", "slide_sparse_gemm_fused",
+           "slide_packed_sizes_fused", "slide_decompose_fused", "slide_sparse_gemm_fused", "slide_sparse_gemm_fused_ws",
            "slide_static_scratch_bytes", "slide_sparse_gemm_static",
            "ss_status_string", "slide_format_version")
 
@@ -58,6 +58,7 @@ def load():
     lib.slide_packed_sizes_fused.argtypes = [i64, i64, i32, i32, ctypes.POINTER(sz), ctypes.POINTER(sz)]
     lib.slide_decompose_fused.argtypes = [vp, i64, i64, i32, i32, vp, vp, vp, vp]
     lib.slide_sparse_gemm_fused.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, i32, vp, i64, vp]
+    lib.slide_sparse_gemm_fused_ws.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i64, i32, i32, vp, i64, vp, sz, vp]
     lib.slide_static_scratch_bytes.argtypes = []
     lib.slide_static_scratch_bytes.restype = sz
     lib.slide_sparse_gemm_static.argtypes = [vp, vp, vp, vp, vp, i64, i64, i64, i32, vp, i64, vp]
@@ -230,15 +231,22 @@ def slide_decompose_fused(Wq: torch.Tensor, N: int, dtype: str, count_violations
     return (w_vals, w_meta, viol) if count_violations else (w_vals, w_meta)
 
 
-def slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O: int, K: int, N: int, dtype: str, out=None):
-    """Y[M,O] bf16 = epilogue(Psi(Xq[M, :K]) . W'^T) from unlifted quantised activations (row stride = Xq.stride(0))."""
+def slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O: int, K: int, N: int, dtype: str, out=None, workspace=None):
+    """Y[M,O] bf16 = epilogue(Psi(Xq[M, :K]) . W'^T) from unlifted quantised activations (row stride = Xq.stride(0)).
+    workspace: optional uint8 device tensor (slide_gemm_workspace_bytes(M, O, K, dtype) bytes) that lets the kernels for
+    small and medium M split the k range."""
     M = Xq.shape[0]
     assert Xq.is_cuda and Xq.stride(1) == 1 and Xq.shape[1] >= K
     if out is None:
         out = torch.empty((M, O), dtype=torch.bfloat16, device=Xq.device)
     ldx = Xq.stride(0) if M > 1 else Xq.shape[1]
-    _check(load().slide_sparse_gemm_fused(_ptr(Xq), _ptr(s_x), _ptr(w_vals), _ptr(w_meta), _ptr(s_w), M, O, K, ldx, N,
-                                          DTYPE_CODE[dtype], _ptr(out), out.stride(0), _stream()), "slide_sparse_gemm_fused")
+    if workspace is None:
+        _check(load().slide_sparse_gemm_fused(_ptr(Xq), _ptr(s_x), _ptr(w_vals), _ptr(w_meta), _ptr(s_w), M, O, K, ldx, N,
+                                              DTYPE_CODE[dtype], _ptr(out), out.stride(0), _stream()), "slide_sparse_gemm_fused")
+    else:
+        _check(load().slide_sparse_gemm_fused_ws(_ptr(Xq), _ptr(s_x), _ptr(w_vals), _ptr(w_meta), _ptr(s_w), M, O, K, ldx, N,
+                                                 DTYPE_CODE[dtype], _ptr(out), out.stride(0), _ptr(workspace), workspace.numel(),
+                                                 _stream()), "slide_sparse_gemm_fused_ws")
     return out
 
 

@@ -358,8 +358,8 @@ static ss_status launch_fused(const void* Xq, const float* s_x, const void* w_va
     return launch_status();
 }
 
-extern "C" ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M,
-                                             int64_t O, int64_t K, int64_t ldx, int N, ss_dtype dtype, void* Y, int64_t ldy, void* stream)
+static ss_status fused_gemm(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                            int64_t K, int64_t ldx, int N, ss_dtype dtype, void* Y, int64_t ldy, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!valid_N(N) || N != 4) return SS_ERR_BAD_PATTERN_N;
     if (!valid_dtype(dtype)) return SS_ERR_DTYPE;
@@ -367,6 +367,8 @@ extern "C" ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, c
     if (M < 0 || O < 0 || K <= 0 || (K * es) % KSTEP != 0 || ldx < K || (ldx * es) % 16 != 0 || ldy < O || M > (1 << 24) || ldy >= (1 << 22) ||
         ldx * es > (1 << 23))
         return SS_ERR_SHAPE;
+    if (workspace_bytes > 0 && !workspace) return SS_ERR_NULL;
+    if ((uintptr_t)workspace & 15) return SS_ERR_WORKSPACE;
     if (M == 0 || O == 0) return SS_OK;
     if (!Xq || !w_vals || !w_meta || !Y) return SS_ERR_NULL;
     if (!unscaled(dtype) && (!s_x || !s_w)) return SS_ERR_NULL;
@@ -374,6 +376,10 @@ extern "C" ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, c
     hipStream_t hs = static_cast<hipStream_t>(stream);
     const int U = (int)(K * es / KSTEP);
     const int64_t ldxb = ldx * es;
+    // kernel family by shape, as for the other two GEMMs; the k loop counts super-units of 128 unlifted bytes
+    const ss_plan p = plan_gemm(M, O, U, workspace_bytes);
+    if (p.path == SS_PATH_SKINNY) return launch_sparse_fused_skinny(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, dtype, Y, ldy, workspace, p.S, hs);
+    if (p.path == SS_PATH_MID) return launch_sparse_fused_mid(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, dtype, Y, ldy, workspace, p.S, hs);
 #define SS_F(DT) launch_fused<DT, 4>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, hs)
     switch (dtype) {
     case SS_I8: return SS_F(SS_I8);
@@ -383,4 +389,17 @@ extern "C" ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, c
     }
 #undef SS_F
     return SS_ERR_DTYPE;
+}
+
+extern "C" ss_status slide_sparse_gemm_fused(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M,
+                                             int64_t O, int64_t K, int64_t ldx, int N, ss_dtype dtype, void* Y, int64_t ldy, void* stream)
+{
+    return fused_gemm(Xq, s_x, w_vals, w_meta, s_w, M, O, K, ldx, N, dtype, Y, ldy, nullptr, 0, stream);
+}
+
+extern "C" ss_status slide_sparse_gemm_fused_ws(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M,
+                                                int64_t O, int64_t K, int64_t ldx, int N, ss_dtype dtype, void* Y, int64_t ldy, void* workspace,
+                                                size_t workspace_bytes, void* stream)
+{
+    return fused_gemm(Xq, s_x, w_vals, w_meta, s_w, M, O, K, ldx, N, dtype, Y, ldy, workspace, workspace_bytes, stream);
 }

@@ -32,6 +32,10 @@ constexpr int MD_S_UNIT = MD_TOK + MD_AV + MD_AM;   // 26 KB
 constexpr int MD_D_UNIT = 2 * MD_TOK;               // 32 KB
 constexpr int MD_S_LPU = MD_ROWS_LOADS + 2 + 1;     // direct loads per wavefront and unit
 constexpr int MD_D_LPU = 2 * MD_ROWS_LOADS;
+// fused lifting (6:8): a unit is a super-unit of 128 unlifted bytes = three steps of one panel
+constexpr int MD_F_AV = 3 * 4096, MD_F_AM = 3 * 1024;
+constexpr int MD_F_UNIT = MD_TOK + MD_F_AV + MD_F_AM;   // 31 KB
+constexpr int MD_F_LPU = MD_ROWS_LOADS + 3 + 1;
 
 // per-lane source offsets of the direct loads that fill a [128 x 128 B] swizzled tile; rows beyond the
 // matrix are clamped to its last row (their products are never stored)
@@ -228,8 +232,98 @@ __global__ __launch_bounds__(MD_THREADS) void k_sparse_mid(const uint8_t* __rest
     else mid_store<MM::SCALED>(acc, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo, t0 + wt * 64, lane);
 }
 
+// ---- sparse, lifting applied in the operand read (6:8, weights packed by slide_decompose_fused) --------------
+// Same tile and ring as k_sparse_mid, but the token tile holds UNLIFTED rows (a super-unit of 128 bytes per row and
+// unit, as in the dense kernel) and a unit is three matrix-instruction steps deep: B lane (n, qb) reads the 64 bytes
+// [64 qb, 64 qb + 64) of its row as 16 registers, uses the first eight in step 0, the second eight in step 1 and builds
+// the eight middle windows of step 2 in registers (packed_layout.h, fused_window).  The k loop is as long as the
+// dense kernel's, with three sparse instructions where that one issues four dense ones.
+template <int DT, int RING>
+__global__ __launch_bounds__(MD_THREADS) void k_sparse_fused_mid(const uint8_t* __restrict__ Xq, const float* __restrict__ s_x,
+                                                                 const uint8_t* __restrict__ w_vals, const uint8_t* __restrict__ w_meta,
+                                                                 const float* __restrict__ s_w, int64_t M, int64_t O, int U_all, int64_t ldxb,
+                                                                 uint16_t* __restrict__ Y, int64_t ldy, int tiles_t, void* __restrict__ ws)
+{
+    typedef Mma<DT> MM;
+    constexpr int ES = MM::ES;
+    extern __shared__ __attribute__((aligned(1024))) uint8_t smem[];     // RING units
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
+    const int wo = wave & 1, wt = wave >> 1;
+    const int n = lane & 31, qb = lane >> 5;
+    const int u0 = (int)((int64_t)blockIdx.y * U_all / gridDim.y), U = (int)((int64_t)(blockIdx.y + 1) * U_all / gridDim.y) - u0;
+    const int tile = mid_tile_of_block();
+    const int64_t panel = tile / tiles_t;
+    const int64_t t0 = (int64_t)(tile - panel * tiles_t) * MD_TILE;
+
+    MidRowLoader lb;
+    lb.init(Xq + (int64_t)u0 * ROWB, ldxb, t0, M, wave, lane);
+    // super-unit u of the panel: 12 KB of values [step 3][fragment 4][lane 64][16 B], 3 KB of index words
+    // [step 3][lane 64][fragment 4][4 B]; wavefront w copies value pieces 3w .. 3w + 2 (1 KB each) and 768 bytes
+    // of the index words (lanes 0..47 of one load)
+    const uint8_t* av_src = w_vals + (panel * U_all + u0) * MD_F_AV + wave * 3072;
+    const uint8_t* am_src = w_meta + (panel * U_all + u0) * MD_F_AM + wave * 768;
+    const uint32_t lane16 = lane * 16;
+    auto issue = [&](int u, int slot) {
+        uint8_t* st = smem + slot * MD_F_UNIT;
+        lb.issue((int64_t)u * ROWB, st, wave);
+#pragma unroll
+        for (int i = 0; i < 3; ++i) lds_dma16(av_src + (int64_t)u * MD_F_AV + i * 1024, lane16, st + MD_TOK + wave * 3072 + i * 1024);
+        if (lane < 48) lds_dma16(am_src + (int64_t)u * MD_F_AM, lane16, st + MD_TOK + MD_F_AV + wave * 768);
+    };
+
+    typename MM::acc_t acc[2][2];
+    mid_zero(acc);
+    constexpr int AHEAD = RING - 1;
+#pragma unroll
+    for (int i = 0; i < AHEAD; ++i)
+        if (i < U) issue(i, i);
+    int slot = 0, lslot = AHEAD;
+    for (int u = 0; u < U; ++u) {
+        if (u + AHEAD <= U) wait_vmcnt<(AHEAD - 1) * MD_F_LPU>(); else wait_vmcnt<0>();
+        wg_barrier();
+        if (u + AHEAD < U) issue(u + AHEAD, lslot);
+        const uint8_t* st = smem + slot * MD_F_UNIT;
+        // the lane's 64 unlifted bytes of both token blocks
+        int x[2][16];
+#pragma unroll
+        for (int tb = 0; tb < 2; ++tb) {
+            const int row = wt * 64 + tb * 32 + n;
+#pragma unroll
+            for (int c = 0; c < 4; ++c) {
+                const v4i v = *tile_chunk(st, row, 4 * qb + c);
+#pragma unroll
+                for (int e = 0; e < 4; ++e) x[tb][4 * c + e] = v[e];
+            }
+        }
+#pragma unroll
+        for (int J = 0; J < 3; ++J) {
+            v4i a[2]; v8i b[2];
+            typedef int v2i __attribute__((ext_vector_type(2)));
+            const v2i idx = *reinterpret_cast<const v2i*>(st + MD_TOK + MD_F_AV + (J * 64 + lane) * 16 + wo * 8);
+#pragma unroll
+            for (int f = 0; f < 2; ++f) a[f] = *reinterpret_cast<const v4i*>(st + MD_TOK + ((J * 4 + 2 * wo + f) * 64 + lane) * 16);
+#pragma unroll
+            for (int tb = 0; tb < 2; ++tb)
+#pragma unroll
+                for (int jd = 0; jd < 8; ++jd) {
+                    if (J < 2) b[tb][jd] = x[tb][8 * J + jd];
+                    else if constexpr (ES == 1) b[tb][jd] = (int)__builtin_amdgcn_alignbyte((uint32_t)x[tb][2 * jd + 1], (uint32_t)x[tb][2 * jd], 2);
+                    else b[tb][jd] = x[tb][4 * (jd >> 1) + 1 + (jd & 1)];
+                }
+#pragma unroll
+            for (int f = 0; f < 2; ++f)
+#pragma unroll
+                for (int tb = 0; tb < 2; ++tb) acc[f][tb] = MM::sparse(a[f], b[tb], acc[f][tb], idx[f]);
+        }
+        slot = slot == RING - 1 ? 0 : slot + 1;
+        lslot = lslot == RING - 1 ? 0 : lslot + 1;
+    }
+    if (gridDim.y > 1) mid_store_partial(acc, ws, (int64_t)blockIdx.y * gridDim.x + tile, wave, lane);
+    else mid_store<MM::SCALED>(acc, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo, t0 + wt * 64, lane);
+}
+
 // ---- dense ----------------------------------------------------------------------------------------------
-template <int DT>
+template <int DT, int RING>
 __global__ __launch_bounds__(MD_THREADS) void k_dense_mid(const uint8_t* __restrict__ Xq, const float* __restrict__ s_x, const uint8_t* __restrict__ Wq,
                                                           const float* __restrict__ s_w, int64_t M, int64_t O, int64_t Kb, uint16_t* __restrict__ Y,
                                                           int64_t ldy, int tiles_t, void* __restrict__ ws)
@@ -263,7 +357,7 @@ __global__ __launch_bounds__(MD_THREADS) void k_dense_mid(const uint8_t* __restr
 
     typename MM::acc_t acc[2][2];
     mid_zero(acc);
-    constexpr int AHEAD = MD_D_RING - 1;
+    constexpr int AHEAD = RING - 1;
 #pragma unroll
     for (int i = 0; i < AHEAD; ++i)
         if (i < U) issue(i, i);
@@ -298,8 +392,8 @@ __global__ __launch_bounds__(MD_THREADS) void k_dense_mid(const uint8_t* __restr
 #pragma unroll
                 for (int tb = 0; tb < 2; ++tb) acc[f][tb] = MM::dense(a[f], b[tb], acc[f][tb]);
         }
-        slot = slot == MD_D_RING - 1 ? 0 : slot + 1;
-        lslot = lslot == MD_D_RING - 1 ? 0 : lslot + 1;
+        slot = slot == RING - 1 ? 0 : slot + 1;
+        lslot = lslot == RING - 1 ? 0 : lslot + 1;
     }
     if (gridDim.y > 1) mid_store_partial(acc, ws, (int64_t)blockIdx.y * gridDim.x + tile, wave, lane);
     else mid_store<MM::SCALED>(acc, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo, t0 + wt * 64, lane);
@@ -333,17 +427,58 @@ static ss_status launch_sparse_mid_dt(const void* XL, const float* s_x, const vo
     return S > 1 ? launch_mid_reduce<DT>(ws, S, ntiles, s_x, s_w, M, O, Y, ldy, tiles_t, stream) : SS_OK;
 }
 
+template <int DT, int RING>
+static ss_status launch_sparse_fused_mid_ring(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M,
+                                              int64_t O, int U, int64_t ldxb, void* Y, int64_t ldy, void* ws, int S, int tiles_t, int64_t ntiles,
+                                              hipStream_t stream)
+{
+    constexpr int lds = RING * MD_F_UNIT;
+    if (allow_dynamic_lds<k_sparse_fused_mid<DT, RING>>(lds) != SS_OK) return SS_ERR_HIP;
+    hipLaunchKernelGGL((k_sparse_fused_mid<DT, RING>), dim3((unsigned)ntiles, (unsigned)S), dim3(MD_THREADS), lds, stream,
+                       static_cast<const uint8_t*>(Xq), s_x, static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, U,
+                       ldxb, static_cast<uint16_t*>(Y), ldy, tiles_t, ws);
+    return launch_status();
+}
+
+template <int DT>
+static ss_status launch_sparse_fused_mid_dt(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M,
+                                            int64_t O, int U, int64_t ldxb, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream)
+{
+    const int tiles_t = (int)((M + MD_TILE - 1) / MD_TILE);
+    const int64_t ntiles = (O + PANEL - 1) / PANEL * tiles_t;
+    // Ring depth: with more workgroups than compute units a ring of two units (62 KB) lets two workgroups share a
+    // unit's LDS and cover each other's load latency; otherwise a lone workgroup gets the deeper ring.
+    // (measured, INT8: 3584 -> 37888 at M = 128, 296 workgroups: 42 -> 30 us; 3584 -> 4608 at M = 1024: 42 -> 29 us;
+    // 18944 -> 3584 at M = 1024, 224 workgroups: 105 us with two units, 95 with three, 92 with four)
+    const ss_status st = ntiles * S > cu_count()
+        ? launch_sparse_fused_mid_ring<DT, 2>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, tiles_t, ntiles, stream)
+        : launch_sparse_fused_mid_ring<DT, 4>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, tiles_t, ntiles, stream);
+    if (st != SS_OK) return st;
+    return S > 1 ? launch_mid_reduce<DT>(ws, S, ntiles, s_x, s_w, M, O, Y, ldy, tiles_t, stream) : SS_OK;
+}
+
+template <int DT, int RING>
+static ss_status launch_dense_mid_ring(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, void* Y,
+                                       int64_t ldy, void* ws, int S, int tiles_t, int64_t ntiles, hipStream_t stream)
+{
+    constexpr int lds = RING * MD_D_UNIT;
+    if (allow_dynamic_lds<k_dense_mid<DT, RING>>(lds) != SS_OK) return SS_ERR_HIP;
+    hipLaunchKernelGGL((k_dense_mid<DT, RING>), dim3((unsigned)ntiles, (unsigned)S), dim3(MD_THREADS), lds, stream, static_cast<const uint8_t*>(Xq),
+                       s_x, static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, tiles_t, ws);
+    return launch_status();
+}
+
 template <int DT>
 static ss_status launch_dense_mid_dt(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, void* Y,
                                      int64_t ldy, void* ws, int S, hipStream_t stream)
 {
     const int tiles_t = (int)((M + MD_TILE - 1) / MD_TILE);
     const int64_t ntiles = (O + PANEL - 1) / PANEL * tiles_t;
-    constexpr int lds = MD_D_RING * MD_D_UNIT;
-    if (allow_dynamic_lds<k_dense_mid<DT>>(lds) != SS_OK) return SS_ERR_HIP;
-    hipLaunchKernelGGL((k_dense_mid<DT>), dim3((unsigned)ntiles, (unsigned)S), dim3(MD_THREADS), lds, stream, static_cast<const uint8_t*>(Xq), s_x,
-                       static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, tiles_t, ws);
-    if (launch_status() != SS_OK) return SS_ERR_HIP;
+    // ring depth as for the fused sparse kernel: two units (64 KB) where two workgroups can share a compute unit
+    const ss_status st = ntiles * S > cu_count()
+        ? launch_dense_mid_ring<DT, 2>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, tiles_t, ntiles, stream)
+        : launch_dense_mid_ring<DT, MD_D_RING>(Xq, s_x, Wq, s_w, M, O, Kb, Y, ldy, ws, S, tiles_t, ntiles, stream);
+    if (st != SS_OK) return st;
     return S > 1 ? launch_mid_reduce<DT>(ws, S, ntiles, s_x, s_w, M, O, Y, ldy, tiles_t, stream) : SS_OK;
 }
 
@@ -376,6 +511,18 @@ ss_status launch_sparse_mid(const void* XL, const float* s_x, const void* w_vals
     case SS_FP8_E4M3: return launch_sparse_mid_dt<SS_FP8_E4M3>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
     case SS_BF16: return launch_sparse_mid_dt<SS_BF16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
     case SS_FP16: return launch_sparse_mid_dt<SS_FP16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
+    }
+    return SS_ERR_DTYPE;
+}
+
+ss_status launch_sparse_fused_mid(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                                  int U, int64_t ldxb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream)
+{
+    switch (dtype) {
+    case SS_I8: return launch_sparse_fused_mid_dt<SS_I8>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, stream);
+    case SS_FP8_E4M3: return launch_sparse_fused_mid_dt<SS_FP8_E4M3>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, stream);
+    case SS_BF16: return launch_sparse_fused_mid_dt<SS_BF16>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, stream);
+    case SS_FP16: return launch_sparse_fused_mid_dt<SS_FP16>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, stream);
     }
     return SS_ERR_DTYPE;
 }

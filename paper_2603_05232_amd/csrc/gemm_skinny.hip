@@ -114,27 +114,33 @@ __device__ inline void sk_store_partial(const ACC (&acc)[NACC], void* ws, int la
 }
 
 // ---- sparse ---------------------------------------------------------------------------------------------
-// Operands of one unit (two steps of 64 lifted bytes) of one wavefront.
-template <int TB, int FPW> struct SkSparseUnit { v4i a[2][FPW]; int idx[2][FPW]; v4i b[TB][4]; };
+// Operands of one unit of one wavefront.  Lifted input: a unit is 128 lifted bytes = NS = 2 steps of 64 lifted bytes.
+// FUSED (6:8, unlifted input, weights packed by slide_decompose_fused): a unit is a super-unit of 128 unlifted bytes
+// = NS = 3 steps; B lane (n, qb) loads the 64 bytes [64 qb, 64 qb + 64) of its token's super-unit, uses the first
+// 32 in step 0, the second 32 in step 1 and builds the eight middle windows of step 2 in registers
+// (packed_layout.h, fused_window): the k loop is as long as the dense kernel's and the token rows are read once,
+// not 1.5 times.
+template <int TB, int FPW, int NS> struct SkSparseUnit { v4i a[NS][FPW]; int idx[NS][FPW]; v4i b[TB][4]; };
 
-template <int DT, int TB, int FPW, int SK_WAVES>
+template <int DT, int TB, int FPW, int SK_WAVES, bool FUSED>
 __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* __restrict__ XL, const float* __restrict__ s_x,
                                                                const uint8_t* __restrict__ w_vals, const uint8_t* __restrict__ w_meta,
-                                                               const float* __restrict__ s_w, int64_t M, int64_t O, int64_t Kpb,
+                                                               const float* __restrict__ s_w, int64_t M, int64_t O, int U, int64_t ldxb,
                                                                uint16_t* __restrict__ Y, int64_t ldy, void* __restrict__ ws)
 {
     typedef Mma<DT> MM;
     typedef int idx_t __attribute__((ext_vector_type(FPW)));
+    constexpr int NS = FUSED ? 3 : 2;                   // steps per unit
     __shared__ __attribute__((aligned(16))) uint8_t red[(SK_WAVES - 1) * FPW * TB * 16 * 64 * 4];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     constexpr int GROUPS = FRAGS_PER_PANEL / FPW;       // workgroups per panel
     const int64_t panel = blockIdx.x / GROUPS;
     const int f0 = (blockIdx.x % GROUPS) * FPW;         // first fragment of this workgroup
-    const int U = (int)(Kpb / (2 * FRAG_KB));
     // values [panel][step][fragment][lane] 16 B, index words [panel][step][lane][fragment] 4 B
-    const v4i* av = reinterpret_cast<const v4i*>(w_vals) + (panel * 2 * U * FRAGS_PER_PANEL + f0) * 64 + lane;
-    const int* am = reinterpret_cast<const int*>(w_meta) + (panel * 2 * U * 64 + lane) * FRAGS_PER_PANEL + f0;
-    // token rows: lane (n, qb) holds the lifted bytes [32 qb, 32 qb + 32) of token n within a step
+    const v4i* av = reinterpret_cast<const v4i*>(w_vals) + (panel * NS * U * FRAGS_PER_PANEL + f0) * 64 + lane;
+    const int* am = reinterpret_cast<const int*>(w_meta) + (panel * NS * U * 64 + lane) * FRAGS_PER_PANEL + f0;
+    // token rows: lane (n, qb) holds the bytes [32 qb, 32 qb + 32) of token n within a step (lifted input) or
+    // [64 qb, 64 qb + 64) within a super-unit (unlifted input)
     // Lanes whose token does not exist load nothing (their products are never stored): a load instruction costs the
     // memory pipeline by its active lanes, and with a single token 31 of 32 would fetch copies.
     const uint8_t* xb[TB];
@@ -144,12 +150,12 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
         int64_t tok = tb * 32 + (lane & 31);
         live[tb] = tok < M;
         tok = live[tb] ? tok : M - 1;
-        xb[tb] = XL + tok * Kpb + 32 * (lane >> 5);
+        xb[tb] = XL + tok * ldxb + (FUSED ? 64 : 32) * (lane >> 5);
     }
-    auto load = [&](SkSparseUnit<TB, FPW>& R, int u) {
+    auto load = [&](SkSparseUnit<TB, FPW, NS>& R, int u) {
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
-            const int64_t s = 2 * (int64_t)u + h;
+        for (int h = 0; h < NS; ++h) {
+            const int64_t s = NS * (int64_t)u + h;
 #pragma unroll
             for (int f = 0; f < FPW; ++f) R.a[h][f] = av[s * (FRAGS_PER_PANEL * 64) + f * 64];
             if constexpr (FPW == 1) R.idx[h][0] = am[s * (64 * FRAGS_PER_PANEL)];
@@ -162,13 +168,38 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
 #pragma unroll
         for (int tb = 0; tb < TB; ++tb)
             if (live[tb]) {
+                if constexpr (FUSED) {
+                    const v4i* p = reinterpret_cast<const v4i*>(xb[tb] + (int64_t)u * KSTEP);
 #pragma unroll
-                for (int h = 0; h < 2; ++h) {
-                    const v4i* p = reinterpret_cast<const v4i*>(xb[tb] + (2 * (int64_t)u + h) * FRAG_KB);
-                    R.b[tb][2 * h] = p[0];
-                    R.b[tb][2 * h + 1] = p[1];
+                    for (int c = 0; c < 4; ++c) R.b[tb][c] = p[c];
+                } else {
+#pragma unroll
+                    for (int h = 0; h < 2; ++h) {
+                        const v4i* p = reinterpret_cast<const v4i*>(xb[tb] + (2 * (int64_t)u + h) * FRAG_KB);
+                        R.b[tb][2 * h] = p[0];
+                        R.b[tb][2 * h + 1] = p[1];
+                    }
                 }
             }
+    };
+    // B operand of step h from the unit's token registers
+    auto operand = [&](const v4i (&x)[4], int h) -> v8i {
+        if (!FUSED || h < 2) {
+            const v4i lo = x[2 * h], hi = x[2 * h + 1];
+            return v8i{lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+        }
+        v8i b;
+#pragma unroll
+        for (int jd = 0; jd < 8; ++jd) {
+            if constexpr (MM::ES == 1) {                 // bytes 2..5 of block jd (registers 2 jd, 2 jd + 1)
+                const int r0 = 2 * jd, r1 = 2 * jd + 1;
+                b[jd] = (int)__builtin_amdgcn_alignbyte((uint32_t)x[r1 >> 2][r1 & 3], (uint32_t)x[r0 >> 2][r0 & 3], 2);
+            } else {                                     // elements 2..5 of block jd >> 1: its registers 1 and 2
+                const int r = 4 * (jd >> 1) + 1 + (jd & 1);
+                b[jd] = x[r >> 2][r & 3];
+            }
+        }
+        return b;
     };
     typename MM::acc_t acc[FPW * TB];
 #pragma unroll
@@ -176,7 +207,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
     // A wavefront's units go through a ring of D register stages, all of them in flight: a lone wavefront's chain of
     // load round trips (a few units, each a trip to HBM) is what bounds the kernel where workgroups are single fragments.
     constexpr int D = SK_DEPTH<FPW, TB>;
-    SkSparseUnit<TB, FPW> st[D];
+    SkSparseUnit<TB, FPW, NS> st[D];
 #pragma unroll
     for (int d = 0; d < D; ++d)
 #pragma unroll
@@ -195,11 +226,10 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
             const int uu = u + d * SK_WAVES;
             if (uu < u_end) {
 #pragma unroll
-                for (int h = 0; h < 2; ++h)
+                for (int h = 0; h < NS; ++h)
 #pragma unroll
                     for (int tb = 0; tb < TB; ++tb) {
-                        const v4i lo = st[d].b[tb][2 * h], hi = st[d].b[tb][2 * h + 1];
-                        const v8i b = {lo[0], lo[1], lo[2], lo[3], hi[0], hi[1], hi[2], hi[3]};
+                        const v8i b = operand(st[d].b[tb], h);
 #pragma unroll
                         for (int f = 0; f < FPW; ++f) acc[f * TB + tb] = MM::sparse(st[d].a[h][f], b, acc[f * TB + tb], st[d].idx[h][f]);
                     }
@@ -390,23 +420,24 @@ static int pick_fpw(int64_t frags)
     return fpw;
 }
 
-template <int DT, int TB, int FPW>
+// U units of 128 bytes per token row (lifted rows, or unlifted rows when FUSED), ldxb bytes between rows
+template <int DT, int TB, int FPW, bool FUSED>
 static ss_status launch_sparse_one(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
-                                   int64_t Kpb, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream)
+                                   int U, int64_t ldxb, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream)
 {
     const int64_t npanels = (O + PANEL - 1) / PANEL;
     const unsigned grid = (unsigned)(npanels * (FRAGS_PER_PANEL / FPW));
     if (FPW == 1 && (int)grid < cu_count()) {
-        hipLaunchKernelGGL((k_sparse_skinny<DT, TB, 1, 8>), dim3(grid, (unsigned)S), dim3(512), 0, stream, static_cast<const uint8_t*>(XL), s_x,
-                           static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy, ws);
+        hipLaunchKernelGGL((k_sparse_skinny<DT, TB, 1, 8, FUSED>), dim3(grid, (unsigned)S), dim3(512), 0, stream, static_cast<const uint8_t*>(XL), s_x,
+                           static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, U, ldxb, static_cast<uint16_t*>(Y), ldy, ws);
         const ss_status first = launch_status();       // reading the status clears it: keep it
         if (first != SS_OK || S <= 1) return first;
         hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
                            static_cast<uint16_t*>(Y), ldy);
     } else {
         // several fragments per workgroup; with S > 1 the k range is split over S workgroups per fragment group
-        hipLaunchKernelGGL((k_sparse_skinny<DT, TB, FPW, 4>), dim3(grid, (unsigned)S), dim3(256), 0, stream, static_cast<const uint8_t*>(XL), s_x,
-                           static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, Kpb, static_cast<uint16_t*>(Y), ldy, ws);
+        hipLaunchKernelGGL((k_sparse_skinny<DT, TB, FPW, 4, FUSED>), dim3(grid, (unsigned)S), dim3(256), 0, stream, static_cast<const uint8_t*>(XL), s_x,
+                           static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, U, ldxb, static_cast<uint16_t*>(Y), ldy, ws);
         const ss_status first = launch_status();
         if (first != SS_OK || S <= 1) return first;
         hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3((unsigned)(npanels * FRAGS_PER_PANEL)), dim3(64 * TB), 0, stream,
@@ -464,18 +495,18 @@ static int panel_splits(int64_t O, int64_t units, int cap)
 }
 
 // token blocks of 32: 1 (M <= 32) or 2 (M <= 64).  S = the ranges the workspace has room for.
-template <int DT>
+template <int DT, bool FUSED>
 static ss_status launch_sparse_dt(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
-                                  int64_t Kpb, void* Y, int64_t ldy, void* ws, int S, hipStream_t st)
+                                  int U, int64_t ldxb, void* Y, int64_t ldy, void* ws, int S, hipStream_t st)
 {
     const int64_t frags = (O + PANEL - 1) / PANEL * FRAGS_PER_PANEL;
     int fpw = pick_fpw(frags);
     // Long rows on few panels: whole panels per workgroup (the token rows are read once per 128 channels instead of once
     // per 32) with the k range split over enough workgroups to fill the chip; otherwise S only applies to single fragments.
-    const int s4 = panel_splits(O, Kpb / KSTEP, S);
-    int s_use = fpw == 1 ? frag_splits(M, O, Kpb / KSTEP, S) : 1;
+    const int s4 = panel_splits(O, U, S);
+    int s_use = fpw == 1 ? frag_splits(M, O, U, S) : 1;
     if (s4 > 1) { fpw = 4; s_use = s4; }
-#define SS_GO(TB, FPW) return launch_sparse_one<DT, TB, FPW>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, s_use, st)
+#define SS_GO(TB, FPW) return launch_sparse_one<DT, TB, FPW, FUSED>(XL, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, s_use, st)
     if (M <= 32) { if (fpw == 4) SS_GO(1, 4); if (fpw == 2) SS_GO(1, 2); SS_GO(1, 1); }
     if (fpw == 4) SS_GO(2, 4);
     if (fpw == 2) SS_GO(2, 2);
@@ -519,11 +550,24 @@ size_t skinny_workspace_bytes(int64_t M, int64_t O, int S)
 ss_status launch_sparse_skinny(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
                                int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream)
 {
+    const int U = (int)(Kpb / KSTEP);
     switch (dtype) {
-    case SS_I8: return launch_sparse_dt<SS_I8>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
-    case SS_FP8_E4M3: return launch_sparse_dt<SS_FP8_E4M3>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
-    case SS_BF16: return launch_sparse_dt<SS_BF16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
-    case SS_FP16: return launch_sparse_dt<SS_FP16>(XL, s_x, w_vals, w_meta, s_w, M, O, Kpb, Y, ldy, ws, S, stream);
+    case SS_I8: return launch_sparse_dt<SS_I8, false>(XL, s_x, w_vals, w_meta, s_w, M, O, U, Kpb, Y, ldy, ws, S, stream);
+    case SS_FP8_E4M3: return launch_sparse_dt<SS_FP8_E4M3, false>(XL, s_x, w_vals, w_meta, s_w, M, O, U, Kpb, Y, ldy, ws, S, stream);
+    case SS_BF16: return launch_sparse_dt<SS_BF16, false>(XL, s_x, w_vals, w_meta, s_w, M, O, U, Kpb, Y, ldy, ws, S, stream);
+    case SS_FP16: return launch_sparse_dt<SS_FP16, false>(XL, s_x, w_vals, w_meta, s_w, M, O, U, Kpb, Y, ldy, ws, S, stream);
+    }
+    return SS_ERR_DTYPE;
+}
+
+ss_status launch_sparse_fused_skinny(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                                     int U, int64_t ldxb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream)
+{
+    switch (dtype) {
+    case SS_I8: return launch_sparse_dt<SS_I8, true>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, stream);
+    case SS_FP8_E4M3: return launch_sparse_dt<SS_FP8_E4M3, true>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, stream);
+    case SS_BF16: return launch_sparse_dt<SS_BF16, true>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, stream);
+    case SS_FP16: return launch_sparse_dt<SS_FP16, true>(Xq, s_x, w_vals, w_meta, s_w, M, O, U, ldxb, Y, ldy, ws, S, stream);
     }
     return SS_ERR_DTYPE;
 }

@@ -110,6 +110,10 @@ int skinny_splits(int64_t M, int64_t O, int64_t units, size_t ws_bytes);
 size_t skinny_workspace_bytes(int64_t M, int64_t O, int S);
 ss_status launch_sparse_skinny(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
                                int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
+// the same for unlifted activations and weights packed by slide_decompose_fused (6:8): U super-units of 128 bytes per row,
+// ldxb bytes between token rows
+ss_status launch_sparse_fused_skinny(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                                     int U, int64_t ldxb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
 ss_status launch_dense_skinny(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, ss_dtype dtype,
                               void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
 
@@ -126,6 +130,10 @@ ss_status launch_dense_tile(const void* Xq, const float* s_x, const void* Wq, co
 // (mid_workspace_bytes(M, O, S) bytes) and a second kernel adds them in a fixed order.
 ss_status launch_sparse_mid(const void* XL, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
                             int64_t Kpb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
+// the same for unlifted activations and weights packed by slide_decompose_fused (6:8): U super-units of 128 bytes per row,
+// ldxb bytes between token rows
+ss_status launch_sparse_fused_mid(const void* Xq, const float* s_x, const void* w_vals, const void* w_meta, const float* s_w, int64_t M, int64_t O,
+                                  int U, int64_t ldxb, ss_dtype dtype, void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
 ss_status launch_dense_mid(const void* Xq, const float* s_x, const void* Wq, const float* s_w, int64_t M, int64_t O, int64_t Kb, ss_dtype dtype,
                            void* Y, int64_t ldy, void* ws, int S, hipStream_t stream);
 int mid_splits(int64_t M, int64_t O, int64_t units, size_t ws_bytes);

@@ -34,6 +34,48 @@ def test_fused_gemm_int8(M, O, K):
     assert np.array_equal(bits16(Y), ref["Y"])
 
 
+# shapes that take the few-token kernels (M <= 64: one and two token blocks, single fragments, whole panels, eight
+# wavefronts) and the 128 x 128-tile kernels, with and without a workspace (k range split through it)
+SMALL = [(1, 384, 128), (1, 4608, 3584), (7, 640, 1024), (16, 37888 // 8, 512), (32, 130, 2048), (33, 3584, 1024), (64, 260, 18944 // 2),
+         (16, 3584, 18944), (64, 3584, 18944), (65, 512, 512), (128, 4608, 3584), (200, 700, 1152), (256, 3584, 4736), (1024, 1100, 640)]
+
+
+@pytest.mark.parametrize("with_ws", [False, True])
+@pytest.mark.parametrize("M,O,K", SMALL)
+def test_fused_gemm_small_and_mid_int8(M, O, K, with_ws):
+    rng = np.random.default_rng(M * 7 + O)
+    Wq = rng.integers(-127, 128, size=(O, K)).astype(np.int8)
+    keep = np.argsort(rng.random((O, K // 8, 8)), axis=-1) < rng.integers(0, 7, size=(O, K // 8, 1))
+    Wq = (Wq.reshape(O, K // 8, 8) * keep).reshape(O, K).astype(np.int8)
+    Xq = rng.integers(-127, 128, size=(M, K)).astype(np.int8)
+    s_x = rng.uniform(0.01, 0.1, M).astype(np.float32)
+    s_w = rng.uniform(1e-4, 1e-3, O).astype(np.float32)
+    exp = so.epilogue(gemm_ref.gemm_i8_i64(Xq, Wq), s_x, s_w, "i8")
+    w_vals, w_meta = binding.slide_decompose_fused(dev(Wq), N, "i8")
+    ws = None
+    if with_ws:
+        nbytes = binding.slide_gemm_workspace_bytes(M, O, K, "i8")
+        ws = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=DEV)
+    Y = binding.slide_sparse_gemm_fused(dev(Xq), dev(s_x), w_vals, w_meta, dev(s_w), O, K, N, "i8", workspace=ws)
+    assert np.array_equal(bits16(Y), exp)
+
+
+@pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
+@pytest.mark.parametrize("M,O,K", [(1, 640, 1024), (16, 3584, 4096), (48, 260, 2048), (128, 1100, 1152), (300, 256, 8192)])
+def test_fused_gemm_small_and_mid_float(dtype, M, O, K):
+    X = synth.activations(M, K, seed=M + O)
+    W = synth.weights(O, K, seed=M + O)
+    ref = so.linear_reference(X, W, N, dtype)
+    Wq, s_w = binding.slide_prune_quant(dev(W), N, dtype)
+    w_vals, w_meta = binding.slide_decompose_fused(Wq, N, dtype)
+    Xq, s_x = binding.act_lift_quant(dev(X), 2, dtype)
+    nbytes = binding.slide_gemm_workspace_bytes(M, O, K, dtype)
+    ws = torch.empty((max(nbytes, 16),), dtype=torch.uint8, device=DEV)
+    for w in (None, ws):
+        Y = binding.slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O, K, N, dtype, workspace=w)
+        _float_gemm_check(bits16(Y), ref, dtype)
+
+
 def test_fused_gemm_two_rounds_full_output_and_strides():
     """More tiles than compute units (17 x 18 = 306 tiles of 256 x 256: two persistent rounds), ragged edges, random
     sparse supports (windows with 0, 1 and 2 stored values), strided X and Y; every output element against the C oracle."""
