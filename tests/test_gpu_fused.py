@@ -37,7 +37,7 @@ def test_fused_gemm_int8(M, O, K):
 # shapes that take the few-token kernels (M <= 64: one and two token blocks, single fragments, whole panels, eight
 # wavefronts) and the 128 x 128-tile kernels, with and without a workspace (k range split through it)
 SMALL = [(1, 384, 128), (1, 4608, 3584), (7, 640, 1024), (16, 37888 // 8, 512), (32, 130, 2048), (33, 3584, 1024), (64, 260, 18944 // 2),
-         (16, 3584, 18944), (64, 3584, 18944), (65, 512, 512), (128, 4608, 3584), (200, 700, 1152), (256, 3584, 4736), (1024, 1100, 640)]
+         (16, 3584, 18944), (64, 3584, 18944), (65, 512, 512), (100, 256, 128), (129, 300, 256), (70, 130, 384), (128, 4608, 3584), (200, 700, 1152), (256, 3584, 4736), (1024, 1100, 640)]
 
 
 @pytest.mark.parametrize("with_ws", [False, True])
