@@ -29,6 +29,9 @@ PEAK_HBM_GBS = 8000.0
 # constant, not measured by the run that prints it.  It comes from the FETCH_SIZE and WRITE_SIZE counters of two
 # rocprofv3 --pmc runs of this script, each scaled by what the same counter reads for the 256 MiB elementwise copy of
 # --copy-calibration; summary and commands in profiles/gemm_qwen7b_m8192_int8_hbm_traffic.txt.
+# Untimed load before every measurement, in seconds (ahead of the --warmup steps): the device needs about 50 ms under
+# load to reach steady clocks after the idle set-up phase.
+SETTLE_SECONDS = 0.15
 RECORDED_TRAFFIC = {"fused": 1.0481e9, "lifted": 1.2935e9}
 N_PATTERN = 4                      # 6:8
 M_TOKENS = 8192
@@ -302,7 +305,17 @@ def main():
             binding.slide_sparse_gemm(s["Xq"], s["s_xd"], s["w_vals24"], s["w_meta24"], s["s_w24"], s["O"], "i8", out=s["Yd"])
             if ev: ev[i][2].record()
 
+    def settle(step_fn, seconds=SETTLE_SECONDS):
+        """Untimed: keeps the GPU under the load of this step until its clocks have settled.  After an idle period (the
+        host-side set-up above) the first ~50 ms of kernels run 10-20 % slower than the steady state."""
+        t0 = time.perf_counter()
+        while time.perf_counter() - t0 < seconds:
+            for _ in range(5):
+                step_fn()
+            torch.cuda.synchronize()
+
     def timed(step_fn):
+        settle(step_fn)
         for _ in range(args.warmup):
             step_fn()
         torch.cuda.synchronize()
@@ -316,6 +329,7 @@ def main():
         """HIP-event durations (ms) of the quantiser and the GEMM of each layer, averaged over reps
         steps, recorded on the stream the kernels run on."""
         acc = np.zeros((len(state), 2))
+        settle(step_fn)
         for _ in range(reps):
             ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in state]
             step_fn(ev)
@@ -373,6 +387,7 @@ def main():
         "metric": "6:8 INT8 sparse-GEMM TOPS + speedup vs own dense MFMA (Qwen2.5-7B shapes)",
         "value": hw_ops / t_sparse * 1e-12, "unit": "TOPS",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": t_sparse * 1e3,
+        "preconditioning": f"{SETTLE_SECONDS} s of the measured step, untimed, before the warm-up steps of every measurement (clock ramp after idle)",
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "i8", "data": "synthetic",
         "config": {"workload": f"Qwen2.5-7B linears (qkv,o,gate_up,down), 6:8 INT8, M={M} tokens: per-token quantisation + slide_sparse_gemm_fused "
                                "(lifting applied inside the GEMM) per layer",
