@@ -190,6 +190,11 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
         auto super_unit = [&](auto mode_c, int u, int par, int bn) __attribute__((always_inline)) {
             constexpr int MODE = decltype(mode_c)::value;
             constexpr bool NEXT = MODE != IT_LAST;
+            // the first matrix instruction goes out right behind the barrier; the scalar set-up of this super-unit's
+            // direct loads (below) runs in its shadow instead of ahead of it
+            __builtin_amdgcn_sched_barrier(0);
+            mma(acc[0][0], R.aA[0], R.lo[0], R.iA[0]);
+            __builtin_amdgcn_sched_barrier(0);
             const uint32_t a_now = va + par * F_ASTEP, i_now = vi + par * F_ASTEP;               // steps 3u .. 3u+2
             const uint32_t a_nxt = va + (3 - par) * F_ASTEP, i_nxt = vi + (3 - par) * F_ASTEP;     // step 3u+3
             uint32_t vbn[NBF][4];
@@ -243,7 +248,7 @@ __global__ __launch_bounds__(128 * WT) void k_sparse_fused(const uint8_t* __rest
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int i = 0; i < NM; ++i) {
-                mma(acc[i / NBF][i % NBF], R.aA[i / NBF], R.lo[i % NBF], R.iA[i / NBF]);
+                if (i > 0) mma(acc[i / NBF][i % NBF], R.aA[i / NBF], R.lo[i % NBF], R.iA[i / NBF]);
                 __builtin_amdgcn_sched_barrier(0);
                 if (i < 4) R.a[i] = rd(a_now + F_ASTEP + i * 1024);
                 if (i == 4) R.iB = rd(i_now + F_ASTEP);
