@@ -115,6 +115,15 @@ def test_argument_errors_return_codes(lib):
     assert lib.dense_gemm_ws(one, one, one, one, 16, 128, 128, 0, one, 128, None, 1024, None) == 1
     assert lib.slide_sparse_gemm_ws(one, one, one, one, one, 16, 128, 128, 0, one, 128, ctypes.c_void_p(8), 64, None) == 5
     assert lib.slide_sparse_gemm_ws(one, one, one, one, one, 16, 128, 100, 0, one, 128, one, 64, None) == 3
+    # fused lifting: 6:8 only, whole 128-byte rows, ldx >= K; workspace rules as above
+    assert lib.slide_sparse_gemm_fused(one, one, one, one, one, 16, 128, 128, 128, 3, 0, one, 128, None) == 2
+    assert lib.slide_sparse_gemm_fused(one, one, one, one, one, 16, 128, 200, 200, 4, 0, one, 128, None) == 3
+    assert lib.slide_sparse_gemm_fused(one, one, one, one, one, 16, 128, 128, 64, 4, 0, one, 128, None) == 3
+    assert lib.slide_sparse_gemm_fused(None, one, one, one, one, 16, 128, 128, 128, 4, 0, one, 128, None) == 1
+    assert lib.slide_sparse_gemm_fused_ws(one, one, one, one, one, 16, 128, 128, 128, 4, 0, one, 128, ctypes.c_void_p(8), 64, None) == 5
+    assert lib.slide_sparse_gemm_fused_ws(one, one, one, one, one, 16, 128, 128, 128, 4, 0, one, 128, None, 64, None) == 1
+    assert lib.slide_sparse_gemm_fused_ws(None, None, None, None, None, 0, 128, 128, 128, 4, 0, None, 128, None, 0, None) == 0
+    assert lib.slide_decompose_fused(one, 128, 512, 3, 0, one, one, None, None) == 2
     # empty problems are fine and touch nothing
     assert lib.act_lift_quant(None, 0, 0, 64, 64, 4, 0, None, None, None) == 0
     assert lib.dense_gemm(None, None, None, None, 0, 128, 128, 0, None, 128, None) == 0
