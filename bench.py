@@ -56,10 +56,11 @@ def parse():
     ap.add_argument("--vendor-baseline", action="store_true",
                     help="context only: also time torch._int_mm (the vendor library's INT8 GEMM, int32 output, no scale epilogue) on "
                          "the four layer shapes")
-    ap.add_argument("--sweep", choices=["dtypes_m", "mid_m", "patterns", "llama_block"], default=None,
+    ap.add_argument("--sweep", choices=["dtypes_m", "mid_m", "patterns", "llama_block", "decode"], default=None,
                     help="instead of the headline step, time one of the other benchmark configurations and print its table "
                          "as one JSON line: dtypes_m = INT8/FP8/BF16 at M in {1,16,128,8192} on the Qwen2.5-7B shapes; "
-                         "mid_m = INT8 at M in {64..2048}; patterns = 4:6, 6:8, 8:10 at M=8192 INT8; llama_block = a Llama-3-8B-shaped block "
+                         "mid_m = INT8 at M in {64..2048}; decode = INT8 at M in {1,16} only (the subset of dtypes_m that the decode-kernel "
+                         "profile is taken on); patterns = 4:6, 6:8, 8:10 at M=8192 INT8; llama_block = a Llama-3-8B-shaped block "
                          "forward at M=4096, 6:8 INT8, the four linears chained through torch reference attention / RMSNorm")
     ap.add_argument("--graph", action="store_true",
                     help="sweeps only: time replays of a HIP graph holding the launches instead of eager calls from Python (below "
@@ -149,6 +150,8 @@ def sweep(args, torch, binding, synth, dev):
         return block_sweep(args, torch, synth, dev)
     if args.sweep == "dtypes_m":
         cases = [(dt, M, 4, name, K, O) for dt in ("i8", "fp8", "bf16") for M in (1, 16, 128, 8192) for name, K, O in synth.QWEN25_7B]
+    elif args.sweep == "decode":
+        cases = [("i8", M, 4, name, K, O) for M in (1, 16) for name, K, O in synth.QWEN25_7B]
     elif args.sweep == "mid_m":
         cases = [("i8", M, 4, name, K, O) for M in (64, 128, 256, 512, 1024, 2048) for name, K, O in synth.QWEN25_7B]
     elif args.sweep == "patterns":

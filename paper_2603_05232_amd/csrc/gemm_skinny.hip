@@ -378,33 +378,66 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* _
     }
 }
 
-// Split k (single-fragment workgroups only): sum of the S partial accumulators of fragment blockIdx.x in range order
-// and the scale epilogue; thread (tb, lane) owns one block.  PANEL_ORDER: fragment F is fragment F % 4 of weight panel
-// F / 4 (channels panel * 128 + 64 h + 16 (F % 4) + r); otherwise it is channels 32 F + 16 h + r.
+// Split k: sum of the S partial accumulators of fragment blockIdx.x in range order and the scale epilogue.  Thread
+// (tb, register quad r4, lane) owns four consecutive channels of one token, so a range costs it one 16-byte load and
+// the loads of up to eight ranges are in flight at once: the kernel is one or two memory round trips long.
+// PANEL_ORDER: fragment F is fragment F % 4 of weight panel F / 4 (channels panel * 128 + 64 h + 16 (F % 4) + r);
+// otherwise it is channels 32 F + 16 h + r.
 template <int DT, int TB, bool PANEL_ORDER>
-__global__ __launch_bounds__(64 * TB) void k_skinny_reduce(const v4i* __restrict__ ws, int S, const float* __restrict__ s_x,
-                                                          const float* __restrict__ s_w, int64_t M, int64_t O, uint16_t* __restrict__ Y, int64_t ldy)
+__global__ __launch_bounds__(256 * TB) void k_skinny_reduce(const v4i* __restrict__ ws, int S, const float* __restrict__ s_x,
+                                                           const float* __restrict__ s_w, int64_t M, int64_t O, uint16_t* __restrict__ Y, int64_t ldy)
 {
     typedef Mma<DT> MM;
     typedef typename MM::acc_t acc_t;
     typedef decltype(acc_t{}[0] + acc_t{}[0]) elem_t;
     typedef elem_t quad_t __attribute__((ext_vector_type(4)));
     const int64_t F = blockIdx.x, nfrag = gridDim.x;
-    const int tb = threadIdx.x >> 6, lane = threadIdx.x & 63, h = lane >> 5;
-    acc_t a;
+    const int lane = threadIdx.x & 63, r4 = (threadIdx.x >> 6) & 3, tb = threadIdx.x >> 8, h = lane >> 5;
+    quad_t a = {0, 0, 0, 0};
+    const v4i* src = ws + ((F * TB + tb) * 4 + r4) * 64 + lane;
+    const int64_t range_stride = nfrag * TB * 4 * 64;
+    int s = 0;
+    for (; s + 8 <= S; s += 8) {
+        quad_t q[8];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) a[r] = 0;
-    for (int s = 0; s < S; ++s) {
-        const v4i* src = ws + (((s * nfrag + F) * TB + tb) * 4) * 64 + lane;
+        for (int d = 0; d < 8; ++d) q[d] = __builtin_bit_cast(quad_t, src[(s + d) * range_stride]);
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            const quad_t q = __builtin_bit_cast(quad_t, src[r4 * 64]);
-#pragma unroll
-            for (int e = 0; e < 4; ++e) a[4 * r4 + e] += q[e];
-        }
+        for (int d = 0; d < 8; ++d) a += q[d];
     }
-    const int64_t o_lane = PANEL_ORDER ? (F >> 2) * PANEL + 64 * h + 16 * (F & 3) : F * 32 + 16 * h;
-    store_block16<MM::SCALED>(a, s_x, s_w, Y, ldy, M, O, o_lane, tb * 32 + (lane & 31));
+    if (s + 4 <= S) {
+        quad_t q[4];
+#pragma unroll
+        for (int d = 0; d < 4; ++d) q[d] = __builtin_bit_cast(quad_t, src[(s + d) * range_stride]);
+#pragma unroll
+        for (int d = 0; d < 4; ++d) a += q[d];
+        s += 4;
+    }
+    {
+        quad_t q[3];
+#pragma unroll
+        for (int d = 0; d < 3; ++d) q[d] = s + d < S ? __builtin_bit_cast(quad_t, src[(s + d) * range_stride]) : quad_t{0, 0, 0, 0};
+#pragma unroll
+        for (int d = 0; d < 3; ++d)
+            if (s + d < S) a += q[d];
+    }
+    const int64_t tok = tb * 32 + (lane & 31);
+    const int64_t o = (PANEL_ORDER ? (F >> 2) * PANEL + 64 * h + 16 * (F & 3) : F * 32 + 16 * h) + 4 * r4;
+    if (tok >= M || o >= O) return;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[e] = (float)a[e];
+        if constexpr (MM::SCALED) v[e] = (v[e] * s_x[tok]) * s_w[o + e < O ? o + e : O - 1];
+    }
+    const uint32_t w0 = pack_bf16x2(v[0], v[1]), w1 = pack_bf16x2(v[2], v[3]);
+    uint16_t* dst = Y + tok * ldy + o;
+    if (o + 4 <= O && (((uintptr_t)dst) & 7) == 0) *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
+    else {
+        const uint32_t w[2] = {w0, w1};
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (o + e < O) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+    }
 }
 
 }  // namespace ss
@@ -432,7 +465,7 @@ static ss_status launch_sparse_one(const void* XL, const float* s_x, const void*
                            static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, U, ldxb, static_cast<uint16_t*>(Y), ldy, ws);
         const ss_status first = launch_status();       // reading the status clears it: keep it
         if (first != SS_OK || S <= 1) return first;
-        hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
+        hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3(grid), dim3(256 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
                            static_cast<uint16_t*>(Y), ldy);
     } else {
         // several fragments per workgroup; with S > 1 the k range is split over S workgroups per fragment group
@@ -440,7 +473,7 @@ static ss_status launch_sparse_one(const void* XL, const float* s_x, const void*
                            static_cast<const uint8_t*>(w_vals), static_cast<const uint8_t*>(w_meta), s_w, M, O, U, ldxb, static_cast<uint16_t*>(Y), ldy, ws);
         const ss_status first = launch_status();
         if (first != SS_OK || S <= 1) return first;
-        hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3((unsigned)(npanels * FRAGS_PER_PANEL)), dim3(64 * TB), 0, stream,
+        hipLaunchKernelGGL((k_skinny_reduce<DT, TB, true>), dim3((unsigned)(npanels * FRAGS_PER_PANEL)), dim3(256 * TB), 0, stream,
                            static_cast<const v4i*>(ws), S, s_x, s_w, M, O, static_cast<uint16_t*>(Y), ldy);
     }
     return launch_status();
@@ -456,7 +489,7 @@ static ss_status launch_dense_one(const void* Xq, const float* s_x, const void* 
                            static_cast<const uint8_t*>(Wq), s_w, M, O, Kb, static_cast<uint16_t*>(Y), ldy, ws);
         const ss_status first = launch_status();
         if (first != SS_OK || S <= 1) return first;
-        hipLaunchKernelGGL((k_skinny_reduce<DT, TB, false>), dim3(grid), dim3(64 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
+        hipLaunchKernelGGL((k_skinny_reduce<DT, TB, false>), dim3(grid), dim3(256 * TB), 0, stream, static_cast<const v4i*>(ws), S, s_x, s_w, M, O,
                            static_cast<uint16_t*>(Y), ldy);
     } else
         hipLaunchKernelGGL((k_dense_skinny<DT, TB, FPW, 4>), dim3(grid), dim3(256), 0, stream, static_cast<const uint8_t*>(Xq), s_x,
