@@ -95,11 +95,13 @@ __device__ inline void mid_store_partial(const ACC (&acc)[2][2], void* ws, int64
 }
 
 // Sum of the S partial accumulators of every tile in range order (bit-reproducible also for fp32) and the
-// scale epilogue.  One workgroup per (tile, wavefront of the GEMM kernel); thread (f, tb, lane) owns one block.
+// scale epilogue.  One workgroup per (tile, wavefront of the GEMM kernel); thread (f, tb, register quad, lane) owns four
+// consecutive channels of one token, so a range costs it one 16-byte load and up to eight ranges are in flight at once.
+constexpr int MD_RED_THREADS = 1024;
 template <int DT>
-__global__ __launch_bounds__(MD_THREADS) void k_mid_reduce(const v4i* __restrict__ ws, int S, int64_t ntiles, const float* __restrict__ s_x,
-                                                           const float* __restrict__ s_w, int64_t M, int64_t O, uint16_t* __restrict__ Y,
-                                                           int64_t ldy, int tiles_t)
+__global__ __launch_bounds__(MD_RED_THREADS) void k_mid_reduce(const v4i* __restrict__ ws, int S, int64_t ntiles, const float* __restrict__ s_x,
+                                                               const float* __restrict__ s_w, int64_t M, int64_t O, uint16_t* __restrict__ Y,
+                                                               int64_t ldy, int tiles_t)
 {
     typedef Mma<DT> MM;
     typedef typename MM::acc_t acc_t;
@@ -107,37 +109,36 @@ __global__ __launch_bounds__(MD_THREADS) void k_mid_reduce(const v4i* __restrict
     typedef elem_t quad_t __attribute__((ext_vector_type(4)));
     const int64_t tile = blockIdx.x / MD_WAVES;
     const int wave = blockIdx.x % MD_WAVES, wo = wave & 1, wt = wave >> 1;
-    const int ft = threadIdx.x >> 6, lane = threadIdx.x & 63, f = ft >> 1, tb = ft & 1;
-    acc_t a;
-#pragma unroll
-    for (int r = 0; r < 16; ++r) a[r] = 0;
-    const v4i* src = ws + ((tile * MD_WAVES + wave) * 16 + ft * 4) * 64 + lane;
+    const int lane = threadIdx.x & 63, r4 = (threadIdx.x >> 6) & 3, ft = threadIdx.x >> 8, f = ft >> 1, tb = ft & 1;
+    quad_t a = {0, 0, 0, 0};
+    const v4i* src = ws + ((tile * MD_WAVES + wave) * 16 + ft * 4 + r4) * 64 + lane;
     const int64_t range_stride = ntiles * MD_WAVES * 16 * 64;             // 16-byte groups between consecutive k ranges
-    // four ranges per trip: sixteen loads in flight per thread, added in range order
     int s = 0;
-    for (; s + 4 <= S; s += 4) {
-        quad_t q[4][4];
+    for (; s + 8 <= S; s += 8) {
+        quad_t q[8];
 #pragma unroll
-        for (int d = 0; d < 4; ++d)
+        for (int d = 0; d < 8; ++d) q[d] = __builtin_bit_cast(quad_t, src[(s + d) * range_stride]);
 #pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4) q[d][r4] = __builtin_bit_cast(quad_t, src[(s + d) * range_stride + r4 * 64]);
-#pragma unroll
-        for (int d = 0; d < 4; ++d)
-#pragma unroll
-            for (int r4 = 0; r4 < 4; ++r4)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) a[4 * r4 + e] += q[d][r4][e];
+        for (int d = 0; d < 8; ++d) a += q[d];
     }
-    for (; s < S; ++s) {
+    if (s + 4 <= S) {
+        quad_t q[4];
 #pragma unroll
-        for (int r4 = 0; r4 < 4; ++r4) {
-            const quad_t q = __builtin_bit_cast(quad_t, src[s * range_stride + r4 * 64]);
+        for (int d = 0; d < 4; ++d) q[d] = __builtin_bit_cast(quad_t, src[(s + d) * range_stride]);
 #pragma unroll
-            for (int e = 0; e < 4; ++e) a[4 * r4 + e] += q[e];
-        }
+        for (int d = 0; d < 4; ++d) a += q[d];
+        s += 4;
+    }
+    {
+        quad_t q[3];
+#pragma unroll
+        for (int d = 0; d < 3; ++d) q[d] = s + d < S ? __builtin_bit_cast(quad_t, src[(s + d) * range_stride]) : quad_t{0, 0, 0, 0};
+#pragma unroll
+        for (int d = 0; d < 3; ++d)
+            if (s + d < S) a += q[d];
     }
     const int64_t panel = tile / tiles_t, t0 = (tile - panel * tiles_t) * MD_TILE;
-    store_block16<MM::SCALED>(a, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo + 64 * (lane >> 5) + 16 * f, t0 + wt * 64 + tb * 32 + (lane & 31));
+    store_quad4<MM::SCALED>(a, s_x, s_w, Y, ldy, M, O, panel * PANEL + 32 * wo + 64 * (lane >> 5) + 16 * f + 4 * r4, t0 + wt * 64 + tb * 32 + (lane & 31));
 }
 
 // Tile of this workgroup.  Workgroup ids go round-robin over the 8 XCDs; when the tile count allows, the tiles are
@@ -407,7 +408,7 @@ template <int DT>
 static ss_status launch_mid_reduce(const void* ws, int S, int64_t ntiles, const float* s_x, const float* s_w, int64_t M, int64_t O, void* Y,
                                    int64_t ldy, int tiles_t, hipStream_t stream)
 {
-    hipLaunchKernelGGL((k_mid_reduce<DT>), dim3((unsigned)(ntiles * MD_WAVES)), dim3(MD_THREADS), 0, stream, static_cast<const v4i*>(ws), S, ntiles,
+    hipLaunchKernelGGL((k_mid_reduce<DT>), dim3((unsigned)(ntiles * MD_WAVES)), dim3(MD_RED_THREADS), 0, stream, static_cast<const v4i*>(ws), S, ntiles,
                        s_x, s_w, M, O, static_cast<uint16_t*>(Y), ldy, tiles_t);
     return launch_status();
 }

@@ -420,24 +420,8 @@ __global__ __launch_bounds__(256 * TB) void k_skinny_reduce(const v4i* __restric
         for (int d = 0; d < 3; ++d)
             if (s + d < S) a += q[d];
     }
-    const int64_t tok = tb * 32 + (lane & 31);
     const int64_t o = (PANEL_ORDER ? (F >> 2) * PANEL + 64 * h + 16 * (F & 3) : F * 32 + 16 * h) + 4 * r4;
-    if (tok >= M || o >= O) return;
-    float v[4];
-#pragma unroll
-    for (int e = 0; e < 4; ++e) {
-        v[e] = (float)a[e];
-        if constexpr (MM::SCALED) v[e] = (v[e] * s_x[tok]) * s_w[o + e < O ? o + e : O - 1];
-    }
-    const uint32_t w0 = pack_bf16x2(v[0], v[1]), w1 = pack_bf16x2(v[2], v[3]);
-    uint16_t* dst = Y + tok * ldy + o;
-    if (o + 4 <= O && (((uintptr_t)dst) & 7) == 0) *reinterpret_cast<uint2*>(dst) = make_uint2(w0, w1);
-    else {
-        const uint32_t w[2] = {w0, w1};
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            if (o + e < O) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
-    }
+    store_quad4<MM::SCALED>(a, s_x, s_w, Y, ldy, M, O, o, tb * 32 + (lane & 31));
 }
 
 }  // namespace ss

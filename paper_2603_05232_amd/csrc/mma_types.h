@@ -101,6 +101,29 @@ __device__ inline void store_block16(const ACC& a, const float* __restrict__ s_x
     }
 }
 
+// Epilogue of four consecutive channels o .. o + 3 of token tok held by one thread (the split-k reduce kernels):
+// Y = bf16((float(a) * s_x[tok]) * s_w[o]) (SCALED) or bf16(a).  Out-of-range tokens and channels are skipped.
+template <bool SCALED, typename QUAD>
+__device__ inline void store_quad4(const QUAD& a, const float* __restrict__ s_x, const float* __restrict__ s_w, uint16_t* __restrict__ Y,
+                                   int64_t ldy, int64_t M, int64_t O, int64_t o, int64_t tok)
+{
+    if (tok >= M || o >= O) return;
+    float v[4];
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        v[e] = (float)a[e];
+        if constexpr (SCALED) v[e] = (v[e] * s_x[tok]) * s_w[o + e < O ? o + e : O - 1];
+    }
+    const uint32_t w[2] = {pack_bf16x2(v[0], v[1]), pack_bf16x2(v[2], v[3])};
+    uint16_t* dst = Y + tok * ldy + o;
+    if (o + 4 <= O && (((uintptr_t)dst) & 7) == 0) *reinterpret_cast<uint2*>(dst) = make_uint2(w[0], w[1]);
+    else {
+#pragma unroll
+        for (int e = 0; e < 4; ++e)
+            if (o + e < O) dst[e] = (uint16_t)(w[e >> 1] >> (16 * (e & 1)));
+    }
+}
+
 // Kernels for few tokens (gemm_skinny.hip): one workgroup per 32..128 output channels streams their weights once.
 // With S > 1 (only where every workgroup is a single 32-channel fragment and there are fewer of them than compute
 // units) the k range is split over S workgroups per fragment; partial sums go through `ws`
