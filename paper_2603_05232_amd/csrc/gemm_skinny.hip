@@ -97,13 +97,13 @@ __device__ inline void sk_store(const ACC (&acc)[TB], const float* __restrict__ 
     }
 }
 
-// Split k: the raw accumulators of k range blockIdx.y of workgroup blockIdx.x go to the workspace as
-// ws[range][workgroup][accumulator][register quad][lane] 16-byte groups.
+// Split k: the raw accumulators of k range blockIdx.y of workgroup column `col` (0 .. gridDim.x - 1) go to the workspace as
+// ws[range][column][accumulator][register quad][lane] 16-byte groups.
 template <typename ACC, int NACC>
-__device__ inline void sk_store_partial(const ACC (&acc)[NACC], void* ws, int lane)
+__device__ inline void sk_store_partial(const ACC (&acc)[NACC], void* ws, int col, int lane)
 {
     typedef decltype(acc[0][0] + acc[0][0]) elem_t;
-    v4i* dst = static_cast<v4i*>(ws) + (((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * NACC * 4) * 64 + lane;
+    v4i* dst = static_cast<v4i*>(ws) + (((int64_t)blockIdx.y * gridDim.x + col) * NACC * 4) * 64 + lane;
 #pragma unroll
     for (int i = 0; i < NACC; ++i)
 #pragma unroll
@@ -134,8 +134,17 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
     __shared__ __attribute__((aligned(16))) uint8_t red[(SK_WAVES - 1) * FPW * TB * 16 * 64 * 4];
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), lane = threadIdx.x & 63;
     constexpr int GROUPS = FRAGS_PER_PANEL / FPW;       // workgroups per panel
-    const int64_t panel = blockIdx.x / GROUPS;
-    const int f0 = (blockIdx.x % GROUPS) * FPW;         // first fragment of this workgroup
+    // Workgroup -> (panel, fragment group).  Workgroup ids go round-robin over the 8 XCDs; the GROUPS workgroups of a panel
+    // read the same index-word lines (4 bytes per lane and fragment out of 16) and the same token rows, so they are placed
+    // on one XCD, where the second to fourth of them hit in its L2 (single-fragment workgroups on 3584 -> 4608 fetched
+    // 25 MB for 15.6 MB of packed weights before).  Panels beyond the last whole group of eight keep the plain order.
+    int col = blockIdx.x;
+    if (GROUPS > 1 && ((gridDim.x & 7) == 0 || gridDim.y == 1)) {      // workgroup id mod 8 == blockIdx.x mod 8
+        const int whole = (int)(gridDim.x / (8 * GROUPS)) * (8 * GROUPS);
+        if (col < whole) { const int xcd = col & 7, j = col >> 3; col = ((j / GROUPS) * 8 + xcd) * GROUPS + j % GROUPS; }
+    }
+    const int64_t panel = col / GROUPS;
+    const int f0 = (col % GROUPS) * FPW;                // first fragment of this workgroup
     // values [panel][step][fragment][lane] 16 B, index words [panel][step][lane][fragment] 4 B
     const v4i* av = reinterpret_cast<const v4i*>(w_vals) + (panel * NS * U * FRAGS_PER_PANEL + f0) * 64 + lane;
     const int* am = reinterpret_cast<const int*>(w_meta) + (panel * NS * U * 64 + lane) * FRAGS_PER_PANEL + f0;
@@ -239,7 +248,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_sparse_skinny(const uint8_t* 
     }
     sk_reduce<SK_WAVES, typename MM::acc_t, FPW * TB>(acc, red, wave, lane);
     if (wave == 0) {
-        if (gridDim.y > 1) { sk_store_partial<typename MM::acc_t, FPW * TB>(acc, ws, lane); return; }
+        if (gridDim.y > 1) { sk_store_partial<typename MM::acc_t, FPW * TB>(acc, ws, col, lane); return; }
 #pragma unroll
         for (int f = 0; f < FPW; ++f) {
             typename MM::acc_t part[TB];
@@ -367,7 +376,7 @@ __global__ __launch_bounds__(64 * SK_WAVES) void k_dense_skinny(const uint8_t* _
     }
     sk_reduce<SK_WAVES, typename MM::acc_t, FPW * TB>(acc, red, wave, lane);
     if (wave == 0) {
-        if (gridDim.y > 1) { sk_store_partial<typename MM::acc_t, FPW * TB>(acc, ws, lane); return; }
+        if (gridDim.y > 1) { sk_store_partial<typename MM::acc_t, FPW * TB>(acc, ws, (int)blockIdx.x, lane); return; }
 #pragma unroll
         for (int f = 0; f < FPW; ++f) {
             typename MM::acc_t part[TB];
