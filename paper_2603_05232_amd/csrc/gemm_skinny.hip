@@ -8,10 +8,14 @@
 // four independent load streams, enough of them in flight on every compute unit to keep the memory system
 // busy.  More fragments per workgroup mean fewer re-reads of the token rows (sparse kernel only: the dense
 // kernel's LDS staging makes one fragment per workgroup the faster choice).  Operands go from global memory
-// straight into registers (one unit ahead); partial sums of the four wavefronts meet in LDS in a fixed order (bit-reproducible also
-// for fp32 accumulators) and wavefront 0 applies the scale epilogue.
+// straight into registers (a ring of two to four units per wavefront, all in flight); partial sums of the wavefronts meet
+// in LDS in a fixed order (bit-reproducible also for fp32 accumulators) and wavefront 0 applies the scale epilogue.
+// With a workspace the k range is also split over workgroups (gridDim.y ranges) and k_skinny_reduce adds their partial
+// sums in range order.
 //   sparse: the packed weights are already in operand-register order, 16 bytes + one index word per lane and
 //           step, fully coalesced; no LDS in the main loop.
+//           The same kernel serves the fused path (6:8, unlifted tokens, weights packed by slide_decompose_fused): a unit
+//           is then three steps deep and the lifted B operands are built in registers.
 //   dense:  row-major weights are fetched as whole 128-byte lines (8 rows per load instruction) and turned
 //           into fragments through a wavefront-private 4 KB LDS tile.
 // Tokens are the B operand, read directly from the L2-resident activation rows (whole lines per unit).
