@@ -140,3 +140,78 @@ def test_fused_rejects_other_patterns_and_ragged_k():
     with pytest.raises(binding.SlideSparseError) as e:
         binding.slide_sparse_gemm_fused(Xq, s[:4], w_vals, w_meta, s, 128, 200, 4, "i8")     # K * es not a multiple of 128
     assert e.value.code == 3
+
+
+def _random_fused_cases(n, seed):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        M = int(rng.choice([1, 2, 31, 32, 33, 63, 64, 65, 100, 127, 128, 129, 255, 256, 257, 300, 511, 700]))
+        O = int(rng.choice([1, 31, 32, 33, 127, 128, 129, 255, 256, 257, 384, 513, 700, 1300]))
+        K = 128 * int(rng.integers(1, 20))
+        out.append((M, O, K, bool(rng.integers(0, 2))))
+    return out
+
+
+@pytest.mark.parametrize("M,O,K,with_ws", _random_fused_cases(28, seed=606))
+def test_fused_random_shapes_int8_end_to_end(M, O, K, with_ws):
+    """The fused path from fp32 inputs on shapes around every token-block, fragment, tile and kernel-family boundary:
+    prune + quantise, fused packing, quantisation, fused GEMM; bit-exact against the oracle's linear layer."""
+    X = synth.activations(M, K, seed=M + O + K, n_outliers=2)
+    W = synth.weights(O, K, seed=M + O)
+    ref = so.linear_reference(X, W, N, "i8")
+    Wq, s_w = binding.slide_prune_quant(dev(W), N, "i8")
+    w_vals, w_meta = binding.slide_decompose_fused(Wq, N, "i8")
+    Xq, s_x = binding.act_lift_quant(dev(X), 2, "i8")
+    ws = None
+    if with_ws:
+        ws = torch.empty((max(binding.slide_gemm_workspace_bytes(M, O, K, "i8"), 16),), dtype=torch.uint8, device=DEV)
+    Y = binding.slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O, K, N, "i8", workspace=ws)
+    assert np.array_equal(bits16(Y), ref["Y"])
+
+
+@pytest.mark.parametrize("dtype", ["fp8", "bf16", "fp16"])
+@pytest.mark.parametrize("M,O,K,with_ws", _random_fused_cases(8, seed=909))
+def test_fused_random_shapes_float_end_to_end(dtype, M, O, K, with_ws):
+    es = 1 if dtype == "fp8" else 2
+    K = K if (K * es) % 128 == 0 else K + 64
+    X = synth.activations(M, K, seed=M + O + K, n_outliers=2)
+    W = synth.weights(O, K, seed=M + O)
+    ref = so.linear_reference(X, W, N, dtype)
+    Wq, s_w = binding.slide_prune_quant(dev(W), N, dtype)
+    w_vals, w_meta = binding.slide_decompose_fused(Wq, N, dtype)
+    Xq, s_x = binding.act_lift_quant(dev(X), 2, dtype)
+    ws = None
+    if with_ws:
+        ws = torch.empty((max(binding.slide_gemm_workspace_bytes(M, O, K, dtype), 16),), dtype=torch.uint8, device=DEV)
+    Y = binding.slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O, K, N, dtype, workspace=ws)
+    _float_gemm_check(bits16(Y), ref, dtype)
+
+
+@pytest.mark.parametrize("M", [16, 128, 600])
+def test_fused_hip_graph_replay(M):
+    """Quantisation + fused GEMM (few-token kernel; 128 x 128 tiles with split k and their reduction; persistent tiles)
+    recorded into a HIP graph: nothing is allocated and nothing synchronises.  Every replay is checked against the oracle,
+    with new activations written into the captured input buffer between replays."""
+    K, O = 2048, 640
+    W = synth.weights(O, K, seed=3)
+    Wq, s_w = binding.slide_prune_quant(dev(W), N, "i8")
+    w_vals, w_meta = binding.slide_decompose_fused(Wq, N, "i8")
+    Xs = [synth.activations(M, K, seed=50 + i, n_outliers=2) for i in range(3)]
+    x_in = dev(Xs[0]).clone()
+    Xq, s_x = binding.act_lift_quant(x_in, 2, "i8")              # warm-up outside the capture (first-use set-up)
+    Y = torch.empty((M, O), dtype=torch.bfloat16, device=DEV)
+    n = binding.slide_gemm_workspace_bytes(M, O, K, "i8")
+    ws = torch.empty((max(n, 16),), dtype=torch.uint8, device=DEV)
+    binding.slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O, K, N, "i8", out=Y, workspace=ws)
+    torch.cuda.synchronize()
+    g = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(g):
+        binding.act_lift_quant(x_in, 2, "i8", out=Xq, s_x=s_x)
+        binding.slide_sparse_gemm_fused(Xq, s_x, w_vals, w_meta, s_w, O, K, N, "i8", out=Y, workspace=ws)
+    for i in (1, 2, 0, 1):
+        x_in.copy_(dev(Xs[i]))
+        Y.fill_(-1.0)
+        g.replay()
+        torch.cuda.synchronize()
+        assert np.array_equal(bits16(Y), so.linear_reference(Xs[i], W, N, "i8")["Y"])
