@@ -194,8 +194,8 @@ __global__ __launch_bounds__(G_THREADS) void k_dense(const uint8_t* __restrict__
             static_assert(NSUB == 2 || NSUB == 4, "sub-steps per unit");
             sub_step(t, even, std::true_type{}, loads, lunit);
             if constexpr (NSUB == 4) {
-                wait_lgkm0(); sub_step(t + 1, odd, std::true_type{}, no_loads, 0);
-                wait_lgkm0(); sub_step(t + 2, even, std::true_type{}, no_loads, 0);
+                sub_step(t + 1, odd, std::true_type{}, no_loads, 0);
+                sub_step(t + 2, even, std::true_type{}, no_loads, 0);
             }
         };
 
@@ -209,25 +209,21 @@ __global__ __launch_bounds__(G_THREADS) void k_dense(const uint8_t* __restrict__
         wg_barrier();                                 // unit 0 (and the channel scales) are published
 #pragma unroll
         for (int part = 0; part < NPARTS; ++part) read_part(0, part, 0);
-        wait_lgkm0();
         int t = 0, u = 0;
         unit_head(t, no_loads, 0);
         for (; u + 2 < nunits; ++u, t += NSUB) {      // unit u+1 is in flight, unit u+2 gets requested
             wait_vmcnt<0>();                          // unit u+1 has landed (and the reads of the last sub-step have returned)
             wg_barrier();                             // ... for every wavefront; nobody reads unit u's slot any more
             sub_step(t + NSUB - 1, odd, std::true_type{}, first_half, u + 2);
-            wait_lgkm0();
             unit_head(t + NSUB, second_half, u + 2);
         }
         if (u + 1 < nunits) {                         // the last unit follows without further requests
             wait_vmcnt<0>();
             wg_barrier();
             sub_step(t + NSUB - 1, odd, std::true_type{}, no_loads, 0);
-            wait_lgkm0();
             unit_head(t + NSUB, no_loads, 0);
             t += NSUB;
         }
-        wait_lgkm0();
         // this sub-tile of Y and its token scales (requested here: they arrive behind the last matrix instructions)
         const int64_t o_sub = o_blk + wo * 128, t_sub = t_blk + wt * (32 * NBF);
         const int64_t rows = M - t_sub, cols = O - o_sub;          // <= 0: nothing of this sub-tile exists
@@ -384,7 +380,6 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse(const uint8_t* __restrict_
         wg_barrier();                                 // unit 0 (and the channel scales) are published
 #pragma unroll
         for (int part = 0; part < 9; ++part) read_part(2, 0, part);
-        wait_lgkm0();
         constexpr std::true_type prefetch{};
         int u = 0, slot = 2;
         sub_step(slot, 1, prefetch, no_loads, 0, 0);
@@ -393,7 +388,6 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse(const uint8_t* __restrict_
             wait_vmcnt<S_LPU>();                      // own loads of unit u+1 have landed, own reads of unit u have returned
             wg_barrier();
             sub_step(nslot, 0, prefetch, first_half, u + 3, slot);
-            wait_lgkm0();
             sub_step(nslot, 1, prefetch, second_half, u + 3, slot);
             slot = nslot;
         }
@@ -402,11 +396,9 @@ __global__ __launch_bounds__(G_THREADS) void k_sparse(const uint8_t* __restrict_
             wait_vmcnt<0>();
             wg_barrier();
             sub_step(nslot, 0, prefetch, no_loads, 0, 0);
-            wait_lgkm0();
             sub_step(nslot, 1, prefetch, no_loads, 0, 0);
             slot = nslot;
         }
-        wait_lgkm0();
         // this sub-tile of Y and its token scales (requested here: they arrive behind the last matrix instructions)
         const int64_t o_sub = o_blk + wo * 128, t_sub = t_blk + wt * (32 * NBF);
         const int64_t rows = M - t_sub, cols = O - o_sub;          // <= 0: nothing of this sub-tile exists
