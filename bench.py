@@ -32,7 +32,7 @@ PEAK_HBM_GBS = 8000.0
 # Untimed load before every measurement, in seconds (ahead of the --warmup steps): the device needs about 50 ms under
 # load to reach steady clocks after the idle set-up phase.
 SETTLE_SECONDS = 0.15
-RECORDED_TRAFFIC = {"fused": 1.0419e9, "lifted": 1.3081e9}
+RECORDED_TRAFFIC = {"fused": 1.0443e9, "lifted": 1.2932e9}
 N_PATTERN = 4                      # 6:8
 M_TOKENS = 8192
 
